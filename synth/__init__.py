@@ -1,0 +1,222 @@
+"""Seeded synthetic inputs for the MiCS data path: configurations and generators.
+
+This module serves both the HIP library's tests/bench and the CPU oracle's tests.
+It holds none of the method's arithmetic: values are entries of a quantised-normal
+table picked by an integer hash of (stream key, element index), so a window of any
+buffer can be produced on the host without materialising the rest, and the device
+twin produces identical bytes.
+
+The flat buffers stand in for the transformer layers of the paper's BERT variants
+(Table 1): 12*h^2 + 13*h elements per layer; fp32 master ~ N(0, 0.02), bf16 gradients
+~ N(0, sigma) per configuration (optionally 1 % of elements scaled by 100).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_CSRC = os.path.join(_HERE, "csrc")
+_HOST_LIB = os.path.join(_HERE, "libsynth_host.so")
+_DEV_LIB = os.path.join(_HERE, "libsynth_dev.so")
+
+MASK64 = (1 << 64) - 1
+TABLE_SLOTS = 1 << 16
+
+# stream roles
+ROLE_PARAM, ROLE_MASTER, ROLE_GRAD, ROLE_ACC, ROLE_MISC = 1, 2, 3, 4, 5
+
+
+# ---- configurations ----------------------------------------------------------------
+
+def layer_elems(h: int) -> int:
+    """Elements of one transformer layer with hidden size h and intermediate size 4h
+    (Table 1): 4h^2 attention + 8h^2 feed-forward + 9h biases + 4h LayerNorm."""
+    return 12 * h * h + 13 * h
+
+
+def shard_elems(n: int, p: int, align: int = 8) -> int:
+    per = -(-n // p)
+    return -(-per // align) * align
+
+
+@dataclass(frozen=True)
+class Config:
+    name: str
+    N: int            # logical elements of the flat parameter
+    p: int            # partition group size
+    k: int            # devices per node
+    r: int            # replication factor
+    s: int            # micro-steps per step
+    sigma_grad: float
+    seed: int
+    outlier_frac: float = 0.0
+    outlier_scale: float = 100.0
+    align: int = 8
+    lr: float = 1e-4
+    beta1: float = 0.9
+    beta2: float = 0.999
+    eps: float = 1e-8
+    weight_decay: float = 0.0
+    sigma_master: float = 0.02
+
+    @property
+    def S(self) -> int:
+        return shard_elems(self.N, self.p, self.align)
+
+    @property
+    def N_pad(self) -> int:
+        return self.S * self.p
+
+    @property
+    def nodes(self) -> int:
+        return self.p // self.k
+
+
+CONFIGS = {
+    "tiny": Config("tiny", 1 << 20, p=4, k=2, r=2, s=2, sigma_grad=1e-2, seed=1001),
+    "h2560": Config("h2560", layer_elems(2560), p=8, k=8, r=4, s=4, sigma_grad=1e-3, seed=1002),
+    "h4096": Config("h4096", layer_elems(4096), p=16, k=8, r=2, s=8, sigma_grad=1e-3, seed=1003),
+    # h = 5120 divides by p = 32 exactly, so the ragged tail is made by dropping 13 elements
+    "h5120": Config("h5120", layer_elems(5120) - 13, p=32, k=8, r=2, s=4, sigma_grad=1e-3,
+                    seed=1004, outlier_frac=0.01),
+    # stress variant: odd shard length, chunk starts only element-aligned
+    "h5120_odd": Config("h5120_odd", layer_elems(5120) + 5, p=32, k=8, r=2, s=4, sigma_grad=1e-3,
+                        seed=1004, outlier_frac=0.01, align=1),
+    "h8192": Config("h8192", layer_elems(8192), p=16, k=8, r=8, s=12, sigma_grad=1e-4, seed=1005),
+}
+
+
+# ---- tables --------------------------------------------------------------------------
+
+def _f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Generator-private float32 -> bf16 bits (nearest even) for finite table values."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = u + 0x7FFF + ((u >> 16) & 1)
+    return (u >> 16).astype(np.uint16)
+
+
+def normal_table(sigma: float, elem: str) -> np.ndarray:
+    """65,536 mid-quantiles of N(0, sigma): 'bf16' -> uint16 bit patterns, 'f32' -> float32."""
+    from scipy.special import ndtri
+    q = ndtri((np.arange(TABLE_SLOTS, dtype=np.float64) + 0.5) / TABLE_SLOTS) * float(sigma)
+    f = q.astype(np.float32)
+    if elem == "f32":
+        return f
+    if elem == "bf16":
+        return _f32_to_bf16_bits(f)
+    raise ValueError(elem)
+
+
+def small_int_table(lo: int, hi: int, elem: str) -> np.ndarray:
+    """Table of integers in [lo, hi] (exactly representable): sums over them are exact."""
+    vals = (lo + (np.arange(TABLE_SLOTS) % (hi - lo + 1))).astype(np.float32)
+    return vals if elem == "f32" else _f32_to_bf16_bits(vals)
+
+
+# ---- stream keys -----------------------------------------------------------------------
+
+def _mix64(z: int) -> int:
+    z &= MASK64
+    z ^= z >> 30
+    z = (z * 0xBF58476D1CE4E5B9) & MASK64
+    z ^= z >> 27
+    z = (z * 0x94D049BB133111EB) & MASK64
+    z ^= z >> 31
+    return z
+
+
+def stream_key(seed: int, role: int, c: int = 0, t: int = 0, q: int = 0) -> int:
+    """One independent stream per (seed, role, replica c, micro-step t, rank q)."""
+    z = _mix64(seed)
+    for part in (role, c, t, q):
+        z = _mix64(z + part + 1)
+    return z
+
+
+def outlier_threshold(frac: float) -> int:
+    return int(round(frac * (1 << 32)))
+
+
+# ---- native twins ------------------------------------------------------------------------
+
+def build_host(force: bool = True) -> str:
+    if force or not os.path.exists(_HOST_LIB):
+        tmp = _HOST_LIB + f".tmp{os.getpid()}"
+        subprocess.run(["gcc", "-O2", "-std=c11", "-fopenmp", "-shared", "-fPIC", "-Wall",
+                        "-o", tmp, os.path.join(_CSRC, "synth_host.c")], check=True)
+        os.replace(tmp, _HOST_LIB)
+    return _HOST_LIB
+
+
+def build_device(force: bool = True) -> str:
+    if force or not os.path.exists(_DEV_LIB):
+        tmp = _DEV_LIB + f".tmp{os.getpid()}"
+        subprocess.run(["/opt/rocm/bin/hipcc", "--offload-arch=gfx950", "-O3", "-shared", "-fPIC",
+                        "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                        "-o", tmp, os.path.join(_CSRC, "synth_dev.hip")], check=True)
+        os.replace(tmp, _DEV_LIB)
+    return _DEV_LIB
+
+
+_host = None
+_dev = None
+
+
+def _host_lib():
+    global _host
+    if _host is None:
+        if not os.path.exists(_HOST_LIB):
+            build_host()
+        _host = ctypes.CDLL(_HOST_LIB)
+        _host.synth_fill_host.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_size_t,
+                                          ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p,
+                                          ctypes.c_uint32, ctypes.c_int, ctypes.c_int]
+    return _host
+
+
+def _dev_lib():
+    global _dev
+    if _dev is None:
+        if not os.path.exists(_DEV_LIB):
+            raise RuntimeError(f"{_DEV_LIB} is not built; run __graft_entry__.build() first")
+        _dev = ctypes.CDLL(_DEV_LIB)
+        _dev.synth_fill_device.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_size_t,
+                                           ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p,
+                                           ctypes.c_uint32, ctypes.c_int, ctypes.c_void_p]
+    return _dev
+
+
+def fill_host(key: int, x0: int, n: int, table: np.ndarray,
+              outlier_table: Optional[np.ndarray] = None, outlier_frac: float = 0.0,
+              threads: int = 0) -> np.ndarray:
+    """Elements [x0, x0+n) of stream ``key`` as a numpy array of the table's dtype."""
+    table = np.ascontiguousarray(table)
+    assert table.size == TABLE_SLOTS and table.dtype.itemsize in (2, 4)
+    if outlier_table is not None:
+        outlier_table = np.ascontiguousarray(outlier_table, dtype=table.dtype)
+    out = np.empty(n, dtype=table.dtype)
+    rc = _host_lib().synth_fill_host(
+        out.ctypes.data, x0, n, key, table.ctypes.data,
+        outlier_table.ctypes.data if outlier_table is not None else None,
+        outlier_threshold(outlier_frac) if outlier_table is not None else 0,
+        table.dtype.itemsize, threads or min(16, os.cpu_count() or 1))
+    if rc != 0:
+        raise ValueError("synth_fill_host: bad arguments")
+    return out
+
+
+def fill_device(out_ptr: int, key: int, x0: int, n: int, table_ptr: int, elem_bytes: int,
+                outlier_table_ptr: int = 0, outlier_frac: float = 0.0, stream: int = 0) -> None:
+    """Write elements [x0, x0+n) of stream ``key`` to device memory at ``out_ptr``.
+    ``table_ptr`` / ``outlier_table_ptr`` are device copies of the tables."""
+    rc = _dev_lib().synth_fill_device(
+        out_ptr, x0, n, key, table_ptr, outlier_table_ptr or None,
+        outlier_threshold(outlier_frac) if outlier_table_ptr else 0, elem_bytes, stream or None)
+    if rc != 0:
+        raise RuntimeError(f"synth_fill_device failed (rc={rc})")
