@@ -1,0 +1,285 @@
+#!/usr/bin/env python3
+"""Benchmark of the MiCS per-GPU data path on one MI355X.
+
+A step is one pass of the whole path as ONE rank of a partition group executes it for one
+training iteration of one transformer layer (rank view, the real per-GPU shape):
+
+    a1  hierarchical-gather reorder of the whole bf16 layer           (N elements)
+    a2  s x  reduce-scatter-accumulate of the rank's gradient shard   (S elements, p inputs)
+    a3  replica average over the r accumulator copies                 (S elements)
+    a4  mixed-precision Adam on the shard                             (S elements)
+
+Default workload: hidden size 8192 (805.4 M parameters per layer), p = 16 (2 nodes x k = 8),
+r = 8, s = 12.  All inputs are synthetic, seeded, and resident in HBM before timing; every
+micro-step has its own gradient buffers (19.3 GB), nothing is reused or cached.
+
+Prints one JSON line.  `--view group` times the same kernels over all p shards at once
+(p*S elements per call; the gradient buffers are then shared by the micro-steps because
+s*p*N_pad bf16 would not fit).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBPS = 8000.0   # MI355X HBM3E, published
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="h8192")
+    ap.add_argument("--view", choices=["rank", "group"], default="rank")
+    ap.add_argument("--rank", type=int, default=5, help="which group rank's shard is simulated")
+    ap.add_argument("--blocks-per-cu", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=16 << 20,
+                    help="shard elements the CPU oracle is timed on")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (cross-GPU transport is out of scope); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synth
+    import paper_2205_00119_amd as mics
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = synth.CONFIGS[args.config]
+    p, k, r, s, S, N, n_pad = cfg.p, cfg.k, cfg.r, cfg.s, cfg.S, cfg.N, cfg.N_pad
+    if args.blocks_per_cu:
+        mics.mics_set_blocks_per_cu(args.blocks_per_cu)
+    group = args.view == "group"
+    count = n_pad if group else S                 # elements per a2/a3/a4 call
+    offset = 0 if group else args.rank * S
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+
+    # ---- synthetic inputs, generated on the device ------------------------------------------
+    tab_g = torch.from_numpy(synth.normal_table(cfg.sigma_grad, "bf16").view(np.int16)).to(dev)
+    tab_go = None
+    if cfg.outlier_frac:
+        tab_go = torch.from_numpy(
+            synth.normal_table(cfg.sigma_grad * cfg.outlier_scale, "bf16").view(np.int16)).to(dev)
+    tab_p = torch.from_numpy(synth.normal_table(cfg.sigma_master, "bf16").view(np.int16)).to(dev)
+    tab_w = torch.from_numpy(synth.normal_table(cfg.sigma_master, "f32")).to(dev)
+    sigma_acc = cfg.sigma_grad * (p * s) ** 0.5
+    tab_a = torch.from_numpy(synth.normal_table(sigma_acc, "f32")).to(dev)
+
+    def fill(t, key, x0, table, elem_bytes, outl=None, frac=0.0):
+        synth.fill_device(t.data_ptr(), key, x0, t.numel(), table.data_ptr(), elem_bytes,
+                          outl.data_ptr() if outl is not None else 0, frac, sh)
+
+    # a1: the gathered-but-unordered parameter W = [T_0 .. T_{k-1}], T_l = [C_l, C_{k+l}, ...]
+    W = torch.empty(n_pad, dtype=torch.int16, device=dev)
+    nodes = p // k
+    for g in range(p):
+        j, l = divmod(g, k)
+        slot = (l * nodes + j) * S
+        fill(W[slot:slot + S], synth.stream_key(cfg.seed, synth.ROLE_PARAM, 0, 0, g), 0, tab_p, 2)
+    T_views = [W[l * nodes * S:(l + 1) * nodes * S] for l in range(k)]
+    F = torch.empty(N, dtype=torch.int16, device=dev)
+
+    # a2: per micro-step, p gradient buffers covering the elements this call owns
+    n_sets = 1 if group else s
+    grads = torch.empty((n_sets, p, count), dtype=torch.int16, device=dev)
+    for t in range(n_sets):
+        for q in range(p):
+            fill(grads[t, q], synth.stream_key(cfg.seed, synth.ROLE_GRAD, 0, t, q), offset, tab_g, 2,
+                 tab_go, cfg.outlier_frac)
+    grad_tables = [[grads[t % n_sets, q] for q in range(p)] for t in range(s)]
+
+    # a3: this replica's accumulator plus the r-1 copies that arrive from the other replicas
+    acc = torch.empty(count, dtype=torch.float32, device=dev)
+    others = torch.empty((r - 1, count), dtype=torch.float32, device=dev)
+    for c in range(1, r):
+        fill(others[c - 1], synth.stream_key(cfg.seed, synth.ROLE_ACC, c), offset, tab_a, 4)
+    copies = [acc] + [others[c] for c in range(r - 1)]
+    avg = torch.empty(count, dtype=torch.float32, device=dev)
+    scale = float(np.float32(1.0 / (r * p * s)))
+
+    # a4: master weights, zero moments, bf16 parameter out
+    master = torch.empty(count, dtype=torch.float32, device=dev)
+    fill(master, synth.stream_key(cfg.seed, synth.ROLE_MASTER), offset, tab_w, 4)
+    exp_avg = torch.zeros(count, dtype=torch.float32, device=dev)
+    exp_avg_sq = torch.zeros(count, dtype=torch.float32, device=dev)
+    param = torch.empty(count, dtype=torch.int16, device=dev)
+    hp = dict(lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps, weight_decay=cfg.weight_decay)
+    torch.cuda.synchronize()
+
+    ev = {name: [] for name in ("a1", "a2", "a3", "a4")}
+    all_marks = []
+
+    def step(it, timed):
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(5)] if timed else None
+        if timed:
+            marks[0].record(stream)
+        mics.mics_hier_gather_reorder(F, T_views, N, S, p, k, 2, stream=sh)
+        if timed:
+            marks[1].record(stream)
+        for t in range(s):
+            mics.mics_reduce_scatter_accum(acc, grad_tables[t], 0, count, t > 0, stream=sh)
+        if timed:
+            marks[2].record(stream)
+        mics.mics_replica_average(avg, copies, count, scale, stream=sh)
+        if timed:
+            marks[3].record(stream)
+        mics.mics_adam_shard(master, exp_avg, exp_avg_sq, param, avg, count, step=it, stream=sh, **hp)
+        if timed:
+            marks[4].record(stream)
+            all_marks.append(marks)
+
+    for it in range(1, args.warmup + 1):
+        step(it, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for it in range(args.warmup + 1, args.warmup + args.steps + 1):
+        step(it, True)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    for marks in all_marks:
+        for i, name in enumerate(("a1", "a2", "a3", "a4")):
+            ev[name].append(marks[i].elapsed_time(marks[i + 1]))
+    ms = {name: float(np.mean(ev[name])) for name in ("a1", "a2", "a3", "a4")}
+    ms_step = wall * 1e3 / args.steps
+
+    # ---- algorithmic bytes (what the method must move) ---------------------------------------
+    b_a1 = 2 * 2 * N
+    b_a2_first, b_a2_next = count * (2 * p + 4), count * (2 * p + 8)
+    b_a2 = b_a2_first + (s - 1) * b_a2_next
+    b_a3 = count * (4 * r + 4)
+    b_a4 = count * 30
+    b_step = b_a1 + b_a2 + b_a3 + b_a4
+    gbps = b_step / (ms_step * 1e-3) / 1e9
+    a2_launch_ms = ms["a2"] / s
+    a2_gbps = (b_a2 / s) / (a2_launch_ms * 1e-3) / 1e9
+
+    result = {
+        "metric": "effective HBM GB/s per shard step",
+        "value": round(gbps, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16 in / f32 accumulate",
+        "data": "synthetic",
+        "pct_of_peak_hbm": round(100.0 * gbps / PEAK_HBM_GBPS, 2),
+        "elements_per_s": round(count / (ms_step * 1e-3), 1),
+        "config": {
+            "workload": f"{cfg.name}: one transformer layer h={cfg.name[1:]} N={N}, p={p} "
+                        f"({nodes} nodes x k={k}), r={r}, s={s}, {args.view} view "
+                        f"({count} elements per reduce/average/Adam call)",
+            "view": args.view, "N": N, "S": S, "p": p, "k": k, "r": r, "s": s,
+            "algorithmic_bytes_per_step": b_step,
+        },
+        "kernels": {
+            name: {"ms": round(ms[name], 4),
+                   "GB/s": round(b / (ms[name] * 1e-3) / 1e9, 1)}
+            for name, b in (("a1", b_a1), ("a2", b_a2), ("a3", b_a3), ("a4", b_a4))
+        },
+        "roofline": {
+            "kernel": f"rsa_vec_kernel<{p}> (mics_reduce_scatter_accum)",
+            "bound": "hbm",
+            "achieved": round(a2_gbps, 1),
+            "peak": PEAK_HBM_GBPS,
+            "unit": "GB/s",
+            "frac": round(a2_gbps / PEAK_HBM_GBPS, 4),
+            "avg_launch_ms": round(a2_launch_ms, 5),
+            "algorithmic_bytes_per_launch": b_a2 // s,
+            "traffic": MEASURED_TRAFFIC.get((cfg.name, args.view)),
+        },
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, args)
+    print(json.dumps(result))
+
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (scaled by the same counters on a plain copy); see profiles/.  None = not measured yet.
+MEASURED_TRAFFIC = {}
+
+
+def cpu_baseline(cfg, args):
+    """Time the CPU oracle (as it stands) on a bounded sample of the same workload: the first
+    `m` elements of the rank's shard for a2/a3/a4 and the matching p*m elements for a1."""
+    import numpy as np
+    import oracle
+    import synth
+
+    p, k, r, s = cfg.p, cfg.k, cfg.r, cfg.s
+    m = min(cfg.S, args.cpu_sample)
+    offset = args.rank * cfg.S
+    cores = min(16, os.cpu_count() or 1)
+    gtab = synth.normal_table(cfg.sigma_grad, "bf16")
+    gout = synth.normal_table(cfg.sigma_grad * cfg.outlier_scale, "bf16") if cfg.outlier_frac else None
+    ptab = synth.normal_table(cfg.sigma_master, "bf16")
+    shards = [synth.fill_host(synth.stream_key(cfg.seed, synth.ROLE_PARAM, 0, 0, g), 0, m, ptab)
+              for g in range(p)]
+    T = [np.concatenate([shards[j * k + l] for j in range(p // k)]) for l in range(k)]
+    grads = [[synth.fill_host(synth.stream_key(cfg.seed, synth.ROLE_GRAD, 0, t, q), offset, m, gtab,
+                              gout, cfg.outlier_frac) for q in range(p)] for t in range(s)]
+    atab = synth.normal_table(cfg.sigma_grad * (p * s) ** 0.5, "f32")
+    others = [synth.fill_host(synth.stream_key(cfg.seed, synth.ROLE_ACC, c), offset, m, atab)
+              for c in range(1, r)]
+    w = synth.fill_host(synth.stream_key(cfg.seed, synth.ROLE_MASTER), offset, m,
+                        synth.normal_table(cfg.sigma_master, "f32"))
+    mo, vo = np.zeros(m, np.float32), np.zeros(m, np.float32)
+    acc = np.empty(m, np.float32)
+    scale = float(np.float32(1.0 / (r * p * s)))
+    hp = dict(lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps, weight_decay=cfg.weight_decay)
+    bytes_sample = 4 * p * m + m * ((2 * p + 4) + (s - 1) * (2 * p + 8)) + m * (4 * r + 4) + m * 30
+
+    def one_pass(step):
+        oracle.hier_gather_reorder(T, p * m, m, p)
+        for t in range(s):
+            oracle.reduce_scatter_accum(acc, grads[t], 0, t > 0)
+        avg = oracle.replica_average([acc] + others, scale)
+        oracle.adam_shard(w, mo, vo, avg, step=step, **hp)
+
+    out = {}
+    for label, threads in (("all", cores), ("one", 1)):
+        oracle.set_threads(threads)
+        t0 = time.perf_counter()
+        one_pass(1 if label == "all" else 2)
+        out[label] = time.perf_counter() - t0
+    oracle.set_threads(1)
+    return {
+        "value": round(bytes_sample / out["all"] / 1e9, 2),
+        "unit": "GB/s",
+        "cores": cores,
+        "kind": "oracle",
+        "sample": f"first {m} of the rank's {cfg.S} shard elements (and the matching {p * m} of the "
+                  f"layer for the reorder), one full step, {cores} threads",
+        "seconds": round(out["all"], 3),
+        "value_1_thread": round(bytes_sample / out["one"] / 1e9, 2),
+        "seconds_1_thread": round(out["one"], 3),
+        "elements_per_s": round(m / out["all"], 1),
+    }
+
+
+if __name__ == "__main__":
+    main()

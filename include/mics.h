@@ -1,0 +1,173 @@
+/*
+ * libmics -- the per-GPU data path of MiCS partitioned data parallelism on one
+ * AMD MI355X (gfx950), as a plain C ABI.
+ *
+ * What the library computes is what a rank of a MiCS partition group computes
+ * on its own GPU around the collectives; the wire transfers are not part of it
+ * and the p ranks of a partition group appear here as p buffers:
+ *
+ *   mics_hier_gather_reorder   chunk rearrangement of the three-stage
+ *                              hierarchical all-gather (paper Section 3.3)
+ *   mics_reduce_scatter_accum  reduction arithmetic of the per-micro-step
+ *                              reduce-scatter inside the partition group,
+ *                              accumulated over micro-steps (Section 3.4)
+ *   mics_replica_average       reduction arithmetic of the all-reduce inside
+ *                              the replication group at the accumulation
+ *                              boundary, plus the scaling to a mean (Section 3.4)
+ *   mics_adam_shard            mixed-precision Adam on the rank's shard of the
+ *                              model states (Sections 2.1 and 3.2)
+ *
+ * Notation (paper Section 3.1): k = devices per node, p = devices holding one
+ * model replica (partition group size), s = micro-steps.  r = size of a
+ * replication group (Section 3.2).  Group rank g sits on node j = g div k with
+ * local rank l = g mod k.  S = elements per shard; chunk C_g = shard of rank g;
+ * the flat parameter is [C_0, C_1, ..., C_{p-1}] cut to its logical length.
+ *
+ * Conventions for every entry point
+ *   - Data pointers are DEVICE pointers on the current HIP device.  Pointer
+ *     tables (`const T* const*`) are HOST arrays of device pointers; they are
+ *     read during the call and may be freed or reused as soon as it returns.
+ *   - The caller owns every buffer.  The library allocates no memory, keeps no
+ *     state between calls (apart from the thread-local error text) and never
+ *     synchronises: each call validates its arguments on the host, enqueues
+ *     its kernel(s) on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and returns.  Work is ordered by that stream.
+ *   - Arguments are validated before the first HIP call, so every argument
+ *     error is reported without a GPU.  On error nothing is enqueued.
+ *   - Return value: MICS_OK or a negative MICS_ERR_*; mics_last_error() gives
+ *     the text for the calling thread's most recent failure.
+ *   - bf16 values travel as uint16_t bit patterns (upper half of a binary32).
+ *   - Pointers must be aligned to their element size.  16-byte alignment of
+ *     every buffer (and, for the reorder, a shard size that is a multiple of
+ *     16 bytes) selects the full-speed kernels; anything less aligned is still
+ *     computed correctly by slower kernels.
+ *   - Buffers of one call must not overlap unless stated.
+ */
+#ifndef MICS_H
+#define MICS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MICS_OK                 0
+#define MICS_ERR_INVALID_ARG   (-1)  /* null pointer, bad count, bad geometry, overlap  */
+#define MICS_ERR_ALIGNMENT     (-2)  /* pointer not aligned to its element size          */
+#define MICS_ERR_UNSUPPORTED   (-3)  /* e.g. element width other than 2 or 4 bytes       */
+#define MICS_ERR_HIP           (-4)  /* the HIP runtime refused the launch               */
+
+#define MICS_MAX_GROUP 128           /* largest p, k, r (the paper's largest group: 128) */
+
+/* Library version: major*10000 + minor*100 + patch. */
+int mics_version(void);
+
+/* Text of the calling thread's most recent error ("" if none). Never NULL.
+ * The pointer stays valid until the same thread's next failing call. */
+const char* mics_last_error(void);
+
+/* Elements per shard for a flat buffer of n elements over p ranks:
+ * ceil(n / p) rounded up to a multiple of align_elems (>= 1).  The paper does
+ * not say how a tensor that does not divide by p is padded; this library pads
+ * the tail with elements the caller keeps at zero.  Returns 0 on bad arguments. */
+size_t mics_shard_elems(size_t n, int p, size_t align_elems);
+
+/*
+ * Stage 2 of the hierarchical all-gather (Section 3.3), applied to the whole
+ * gathered parameter: after stage 1 (inter-node all-gather among the devices
+ * of equal local rank) the buffer of local rank l holds the chunks
+ * T_l = [C_l, C_{k+l}, ..., C_{(p/k-1)k+l}] in ascending node order; gathering
+ * those buffers as they are would yield [T_0, ..., T_{k-1}], which for p = 4,
+ * k = 2 is the paper's wrong layout [C0, C2, C1, C3].  This call produces the
+ * correct one:
+ *     dst_flat[(j*k + l)*S + i] = stage1_bufs[l][j*S + i]
+ * for all flat indices below n_valid.  Elements at or beyond n_valid (the
+ * padded tail) are not written.
+ *
+ *   dst_flat     device, n_valid elements of elem_bytes bytes
+ *   stage1_bufs  host table of k device pointers, (p/k)*S elements each; one
+ *                contiguous gathered buffer W is the case bufs[l] = W + l*(p/k)*S
+ *   n_valid      logical length, <= p * shard_elems
+ *   shard_elems  S
+ *   p, k         1 <= k <= p <= MICS_MAX_GROUP, p divisible by k (Section 3.3)
+ *   elem_bytes   2 (bf16/fp16) or 4 (fp32); the data is moved bit-exactly
+ * dst_flat must not overlap any source buffer.  k = 1 and k = p are plain
+ * concatenations.
+ */
+int mics_hier_gather_reorder(void* dst_flat, const void* const* stage1_bufs,
+                             size_t n_valid, size_t shard_elems, int p, int k,
+                             int elem_bytes, void* stream);
+
+/*
+ * Hop 1 of the 2-hop gradient synchronisation (Section 3.4): the reduction
+ * that the reduce-scatter inside the partition group performs on every
+ * micro-step, accumulated across micro-steps into the rank's gradient shard.
+ * For x in [elem_offset, elem_offset + count):
+ *     partial = (((g_0[x] + g_1[x]) + g_2[x]) + ... + g_{p-1}[x])
+ *     acc[x - elem_offset] = (accumulate ? acc[x - elem_offset] : +0) + partial
+ * with every gradient widened exactly from bf16 and every addition a separate
+ * binary32 round-to-nearest-even operation in exactly this order.
+ *
+ *   acc          device, count fp32 elements, read (if accumulate) and written
+ *   grads_bf16   host table of p device pointers; buffer q is rank q's full
+ *                gradient, indexed by the global element index x
+ *   elem_offset  first owned element (rank view: g*S; whole group: 0)
+ *   count        owned elements (rank view: S; whole group: p*S)
+ *   accumulate   0 on the first micro-step of a step, non-zero afterwards
+ */
+int mics_reduce_scatter_accum(float* acc, const uint16_t* const* grads_bf16,
+                              size_t elem_offset, size_t count, int p,
+                              int accumulate, void* stream);
+
+/*
+ * Hop 2 (Section 3.4): the reduction of the all-reduce inside the replication
+ * group at the gradient-accumulation boundary, and the single scaling that
+ * turns the sums of both hops into the global-batch mean:
+ *     out[x] = (((a_0[x] + a_1[x]) + ...) + a_{r-1}[x]) * scale
+ * in binary32, replicas in ascending order, one multiply at the end.  The
+ * paper does not say where the division by the number of summands happens;
+ * here both hops are pure sums and the caller passes scale = 1/(r*p*s)
+ * (or 1/r for a plain replica average).
+ *
+ *   out          device, count fp32; may be the same buffer as acc_copies[0]
+ *   acc_copies   host table of r device pointers, count fp32 each
+ */
+int mics_replica_average(float* out, const float* const* acc_copies,
+                         size_t count, int r, float scale, void* stream);
+
+/*
+ * Parameter update on the rank's shard: Adam in mixed precision (the paper
+ * names the optimizer and its 16 bytes of state per parameter, Section 3.2,
+ * not the rule; this is bias-corrected Adam with decoupled weight decay):
+ *     m' = beta1*m + (1-beta1)*g          v' = beta2*v + (1-beta2)*(g*g)
+ *     w' = w - lr*( (m'/(1-beta1^step)) / (sqrt(v'/(1-beta2^step)) + eps)
+ *                   + weight_decay*w )
+ *     param_bf16 = round-to-nearest-even(w')
+ * computed in binary32 with correctly rounded division and square root and no
+ * fused multiply-add; 1-beta^step is evaluated in double on the host and
+ * rounded to binary32.
+ *
+ *   master, exp_avg, exp_avg_sq   device fp32, count each, updated in place
+ *   param_bf16                    device, count bf16, written; may be NULL
+ *   grad                          device fp32, count, read only
+ *   step                          >= 1, the number of this update
+ */
+int mics_adam_shard(float* master, float* exp_avg, float* exp_avg_sq,
+                    uint16_t* param_bf16, const float* grad, size_t count,
+                    float lr, float beta1, float beta2, float eps,
+                    float weight_decay, int step, void* stream);
+
+/*
+ * Launch-shape knob for measurements (not part of the method): sets how many
+ * workgroups per compute unit the streaming kernels of later calls launch at
+ * most; 0 restores the built-in choice.  Process-wide.  Returns MICS_OK or
+ * MICS_ERR_INVALID_ARG (negative or > 64).
+ */
+int mics_set_blocks_per_cu(int blocks_per_cu);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MICS_H */

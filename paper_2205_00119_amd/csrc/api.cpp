@@ -1,0 +1,213 @@
+// C ABI of libmics: host-side argument validation and dispatch.
+// Every check here runs before the first HIP call, so argument errors are
+// reported identically on a machine without a GPU.
+#include "../../include/mics.h"
+#include "internal.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+
+namespace {
+
+thread_local char g_error[512] = "";
+
+int fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof g_error, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+inline uintptr_t addr(const void* p) { return reinterpret_cast<uintptr_t>(p); }
+inline bool aligned(const void* p, size_t a) { return (addr(p) & (a - 1)) == 0; }
+
+// [a, a+an) and [b, b+bn) share at least one byte
+inline bool overlaps(const void* a, size_t an, const void* b, size_t bn)
+{
+    return an && bn && addr(a) < addr(b) + bn && addr(b) < addr(a) + an;
+}
+
+int hip_fail(const char* what, int err)
+{
+    return fail(MICS_ERR_HIP, "%s: HIP error %d (%s)", what, err, mics::hip_error_text(err));
+}
+
+}  // namespace
+
+extern "C" {
+
+int mics_version(void) { return 100; }
+
+const char* mics_last_error(void) { return g_error; }
+
+size_t mics_shard_elems(size_t n, int p, size_t align_elems)
+{
+    if (p < 1 || align_elems < 1) return 0;
+    size_t per = n / (size_t)p + (n % (size_t)p ? 1 : 0);
+    size_t rem = per % align_elems;
+    return rem ? per + (align_elems - rem) : per;
+}
+
+int mics_set_blocks_per_cu(int blocks_per_cu)
+{
+    if (blocks_per_cu < 0 || blocks_per_cu > 64)
+        return fail(MICS_ERR_INVALID_ARG, "mics_set_blocks_per_cu: %d not in [0, 64]", blocks_per_cu);
+    mics::set_blocks_per_cu(blocks_per_cu);
+    return MICS_OK;
+}
+
+int mics_hier_gather_reorder(void* dst_flat, const void* const* stage1_bufs,
+                             size_t n_valid, size_t shard_elems, int p, int k,
+                             int elem_bytes, void* stream)
+{
+    const char* fn = "mics_hier_gather_reorder";
+    if (elem_bytes != 2 && elem_bytes != 4)
+        return fail(MICS_ERR_UNSUPPORTED, "%s: elem_bytes = %d, must be 2 or 4", fn, elem_bytes);
+    if (p < 1 || p > MICS_MAX_GROUP)
+        return fail(MICS_ERR_INVALID_ARG, "%s: p = %d not in [1, %d]", fn, p, MICS_MAX_GROUP);
+    if (k < 1 || k > p)
+        return fail(MICS_ERR_INVALID_ARG, "%s: k = %d not in [1, p = %d]", fn, k, p);
+    if (p % k != 0)
+        return fail(MICS_ERR_INVALID_ARG, "%s: p = %d is not divisible by k = %d", fn, p, k);
+    const size_t eb = (size_t)elem_bytes;
+    if (shard_elems > SIZE_MAX / eb / (size_t)p)
+        return fail(MICS_ERR_INVALID_ARG, "%s: p * shard_elems * elem_bytes overflows", fn);
+    if (n_valid > (size_t)p * shard_elems)
+        return fail(MICS_ERR_INVALID_ARG, "%s: n_valid = %zu exceeds p * shard_elems = %zu", fn,
+                    n_valid, (size_t)p * shard_elems);
+    if (!stage1_bufs) return fail(MICS_ERR_INVALID_ARG, "%s: stage1_bufs is NULL", fn);
+    if (n_valid == 0) return MICS_OK;
+    if (!dst_flat) return fail(MICS_ERR_INVALID_ARG, "%s: dst_flat is NULL", fn);
+    if (!aligned(dst_flat, eb))
+        return fail(MICS_ERR_ALIGNMENT, "%s: dst_flat not aligned to %d bytes", fn, elem_bytes);
+
+    const size_t shard_bytes = shard_elems * eb;
+    const size_t src_bytes = (size_t)(p / k) * shard_bytes;
+    const size_t dst_bytes = n_valid * eb;
+    mics::PtrTable tab{};
+    bool vec16 = aligned(dst_flat, 16) && shard_bytes % 16 == 0;
+    for (int l = 0; l < k; ++l) {
+        const void* s = stage1_bufs[l];
+        if (!s) return fail(MICS_ERR_INVALID_ARG, "%s: stage1_bufs[%d] is NULL", fn, l);
+        if (!aligned(s, eb))
+            return fail(MICS_ERR_ALIGNMENT, "%s: stage1_bufs[%d] not aligned to %d bytes", fn, l,
+                        elem_bytes);
+        if (overlaps(dst_flat, dst_bytes, s, src_bytes))
+            return fail(MICS_ERR_INVALID_ARG, "%s: dst_flat overlaps stage1_bufs[%d]", fn, l);
+        vec16 = vec16 && aligned(s, 16);
+        tab.ptr[l] = s;
+    }
+    int err = mics::launch_reorder(dst_flat, tab, dst_bytes, shard_bytes, p, k, vec16, stream);
+    return err ? hip_fail(fn, err) : MICS_OK;
+}
+
+int mics_reduce_scatter_accum(float* acc, const uint16_t* const* grads_bf16,
+                              size_t elem_offset, size_t count, int p,
+                              int accumulate, void* stream)
+{
+    const char* fn = "mics_reduce_scatter_accum";
+    if (p < 1 || p > MICS_MAX_GROUP)
+        return fail(MICS_ERR_INVALID_ARG, "%s: p = %d not in [1, %d]", fn, p, MICS_MAX_GROUP);
+    if (!grads_bf16) return fail(MICS_ERR_INVALID_ARG, "%s: grads_bf16 is NULL", fn);
+    if (elem_offset > SIZE_MAX / 4 - count || count > SIZE_MAX / 4)
+        return fail(MICS_ERR_INVALID_ARG, "%s: elem_offset + count overflows", fn);
+    if (count == 0) return MICS_OK;
+    if (!acc) return fail(MICS_ERR_INVALID_ARG, "%s: acc is NULL", fn);
+    if (!aligned(acc, 4)) return fail(MICS_ERR_ALIGNMENT, "%s: acc not aligned to 4 bytes", fn);
+
+    mics::PtrTable tab{};
+    bool vec16 = aligned(acc, 16);
+    for (int q = 0; q < p; ++q) {
+        const uint16_t* g = grads_bf16[q];
+        if (!g) return fail(MICS_ERR_INVALID_ARG, "%s: grads_bf16[%d] is NULL", fn, q);
+        if (!aligned(g, 2))
+            return fail(MICS_ERR_ALIGNMENT, "%s: grads_bf16[%d] not aligned to 2 bytes", fn, q);
+        const uint16_t* first = g + elem_offset;
+        if (overlaps(acc, count * 4, first, count * 2))
+            return fail(MICS_ERR_INVALID_ARG, "%s: acc overlaps grads_bf16[%d]", fn, q);
+        vec16 = vec16 && aligned(first, 16);
+        tab.ptr[q] = first;
+    }
+    int err = mics::launch_reduce_scatter_accum(acc, tab, count, p, accumulate != 0, vec16, stream);
+    return err ? hip_fail(fn, err) : MICS_OK;
+}
+
+int mics_replica_average(float* out, const float* const* acc_copies,
+                         size_t count, int r, float scale, void* stream)
+{
+    const char* fn = "mics_replica_average";
+    if (r < 1 || r > MICS_MAX_GROUP)
+        return fail(MICS_ERR_INVALID_ARG, "%s: r = %d not in [1, %d]", fn, r, MICS_MAX_GROUP);
+    if (!acc_copies) return fail(MICS_ERR_INVALID_ARG, "%s: acc_copies is NULL", fn);
+    if (count > SIZE_MAX / 4) return fail(MICS_ERR_INVALID_ARG, "%s: count overflows", fn);
+    if (count == 0) return MICS_OK;
+    if (!out) return fail(MICS_ERR_INVALID_ARG, "%s: out is NULL", fn);
+    if (!aligned(out, 4)) return fail(MICS_ERR_ALIGNMENT, "%s: out not aligned to 4 bytes", fn);
+
+    mics::PtrTable tab{};
+    bool vec16 = aligned(out, 16);
+    for (int c = 0; c < r; ++c) {
+        const float* a = acc_copies[c];
+        if (!a) return fail(MICS_ERR_INVALID_ARG, "%s: acc_copies[%d] is NULL", fn, c);
+        if (!aligned(a, 4))
+            return fail(MICS_ERR_ALIGNMENT, "%s: acc_copies[%d] not aligned to 4 bytes", fn, c);
+        // the result may replace the first copy exactly (in-place all-reduce), nothing else
+        bool same_as_first = (c == 0 && a == out);
+        if (!same_as_first && overlaps(out, count * 4, a, count * 4))
+            return fail(MICS_ERR_INVALID_ARG, "%s: out overlaps acc_copies[%d]", fn, c);
+        vec16 = vec16 && aligned(a, 16);
+        tab.ptr[c] = a;
+    }
+    int err = mics::launch_replica_average(out, tab, count, r, scale, vec16, stream);
+    return err ? hip_fail(fn, err) : MICS_OK;
+}
+
+int mics_adam_shard(float* master, float* exp_avg, float* exp_avg_sq,
+                    uint16_t* param_bf16, const float* grad, size_t count,
+                    float lr, float beta1, float beta2, float eps,
+                    float weight_decay, int step, void* stream)
+{
+    const char* fn = "mics_adam_shard";
+    if (step < 1) return fail(MICS_ERR_INVALID_ARG, "%s: step = %d, must be >= 1", fn, step);
+    if (!(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f))
+        return fail(MICS_ERR_INVALID_ARG, "%s: beta1 = %g, beta2 = %g must lie in [0, 1)", fn,
+                    (double)beta1, (double)beta2);
+    if (count > SIZE_MAX / 4) return fail(MICS_ERR_INVALID_ARG, "%s: count overflows", fn);
+    if (count == 0) return MICS_OK;
+    if (!master || !exp_avg || !exp_avg_sq || !grad)
+        return fail(MICS_ERR_INVALID_ARG, "%s: master, exp_avg, exp_avg_sq and grad must be non-NULL",
+                    fn);
+    const void* f32[4] = {master, exp_avg, exp_avg_sq, grad};
+    const char* name[4] = {"master", "exp_avg", "exp_avg_sq", "grad"};
+    bool vec16 = true;
+    for (int a = 0; a < 4; ++a) {
+        if (!aligned(f32[a], 4))
+            return fail(MICS_ERR_ALIGNMENT, "%s: %s not aligned to 4 bytes", fn, name[a]);
+        vec16 = vec16 && aligned(f32[a], 16);
+        for (int b = a + 1; b < 4; ++b)
+            if (overlaps(f32[a], count * 4, f32[b], count * 4))
+                return fail(MICS_ERR_INVALID_ARG, "%s: %s overlaps %s", fn, name[a], name[b]);
+        if (param_bf16 && overlaps(f32[a], count * 4, param_bf16, count * 2))
+            return fail(MICS_ERR_INVALID_ARG, "%s: param_bf16 overlaps %s", fn, name[a]);
+    }
+    if (param_bf16) {
+        if (!aligned(param_bf16, 2))
+            return fail(MICS_ERR_ALIGNMENT, "%s: param_bf16 not aligned to 2 bytes", fn);
+        vec16 = vec16 && aligned(param_bf16, 16);
+    }
+
+    mics::AdamScalars hp;
+    hp.lr = lr; hp.beta1 = beta1; hp.beta2 = beta2; hp.eps = eps; hp.weight_decay = weight_decay;
+    hp.one_minus_beta1 = 1.0f - beta1;
+    hp.one_minus_beta2 = 1.0f - beta2;
+    hp.bias_corr1 = (float)(1.0 - std::pow((double)beta1, (double)step));
+    hp.bias_corr2 = (float)(1.0 - std::pow((double)beta2, (double)step));
+    int err = mics::launch_adam(master, exp_avg, exp_avg_sq, param_bf16, grad, count, hp, vec16,
+                                stream);
+    return err ? hip_fail(fn, err) : MICS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,48 @@
+// Internal interface between the host-side argument checks (api.cpp) and the
+// kernel launchers (kernels.hip).  Not installed; the public ABI is include/mics.h.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+
+namespace mics {
+
+constexpr int kMaxGroup = 128;
+
+// Table of device pointers handed to a kernel by value (kernel-argument
+// segment), so no device-side table has to be allocated or copied.
+struct PtrTable {
+    const void* ptr[kMaxGroup];
+};
+
+// Launchers: arguments are already validated.  Each returns 0 or the hipError_t
+// of the failed runtime call (as int) and enqueues on `stream` without waiting.
+
+// vec16: every source, the destination and the shard size are multiples of 16
+// bytes -> direct 128-bit copy; otherwise the LDS-staged re-phasing kernel.
+int launch_reorder(void* dst, const PtrTable& src, size_t n_valid_bytes,
+                   size_t shard_bytes, int p, int k, bool vec16, void* stream);
+
+// grads.ptr[q] already points at element elem_offset of rank q's buffer.
+int launch_reduce_scatter_accum(float* acc, const PtrTable& grads, size_t count,
+                                int p, bool accumulate, bool vec16, void* stream);
+
+int launch_replica_average(float* out, const PtrTable& copies, size_t count,
+                           int r, float scale, bool vec16, void* stream);
+
+struct AdamScalars {
+    float lr, beta1, beta2, eps, weight_decay;
+    float one_minus_beta1, one_minus_beta2;
+    float bias_corr1, bias_corr2;  // 1 - beta^step, double on the host, rounded
+};
+
+int launch_adam(float* master, float* exp_avg, float* exp_avg_sq,
+                uint16_t* param_bf16, const float* grad, size_t count,
+                const AdamScalars& hp, bool vec16, void* stream);
+
+// 0 = built-in choice.
+void set_blocks_per_cu(int n);
+
+const char* hip_error_text(int err);
+
+}  // namespace mics

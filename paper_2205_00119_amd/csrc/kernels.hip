@@ -1,0 +1,652 @@
+// gfx950 kernels of libmics and their launchers.
+//
+// All four steps stream every byte once and do at most a few operations per
+// element, so they are bound by HBM bandwidth, not by the matrix or vector
+// units.  The kernels therefore aim at: 128-bit global loads and stores, many
+// independent loads in flight per lane before the first use, no re-reads, and
+// grids of a few workgroups per compute unit that stride over the data.
+//
+// Arithmetic rules (they make the results reproducible bit for bit):
+//   - no fused multiply-add (-ffp-contract=off and the pragma below),
+//   - sums in the order the header states,
+//   - correctly rounded fp32 division and square root,
+//   - fp32 denormals are kept.
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+
+#include "internal.h"
+
+#pragma clang fp contract(off)
+
+namespace mics {
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kBlock = 256;
+
+// Compile-time sized pointer table for the unrolled kernels (keeps the
+// kernel-argument segment small); the launcher copies out of PtrTable.
+template <int N>
+struct SmallTable {
+    const void* ptr[N];
+};
+
+template <bool NT, typename V>
+__device__ __forceinline__ V ld(const V* p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
+template <bool NT, typename V>
+__device__ __forceinline__ void st(V* p, V v)
+{
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+// bf16 -> fp32 is exact: the bf16 bits are the upper half of the fp32 bits.
+__device__ __forceinline__ float bf16_lo(uint32_t pair) { return __uint_as_float(pair << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t pair) { return __uint_as_float(pair & 0xFFFF0000u); }
+__device__ __forceinline__ float bf16_one(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// fp32 -> bf16, round to nearest even, two at a time (gfx950 converts a pair
+// in one instruction).  Low half = a, high half = b.
+__device__ __forceinline__ uint32_t bf16_pack(float a, float b)
+{
+    f32x2 f = {a, b};
+    bf16x2 h = __builtin_convertvector(f, bf16x2);
+    return __builtin_bit_cast(uint32_t, h);
+}
+
+__device__ __forceinline__ uint16_t bf16_single(float a)
+{
+    __bf16 h = (__bf16)a;
+    return __builtin_bit_cast(uint16_t, h);
+}
+
+// ---------------------------------------------------------------------------
+// Step 1: chunk rearrangement of the hierarchical all-gather (Section 3.3).
+// Chunk g of the result comes from slot g div k of the stage-1 buffer of local
+// rank g mod k.  blockIdx.y = g, blockIdx.x strides over the chunk.
+// ---------------------------------------------------------------------------
+
+// All addresses and the shard size are multiples of 16 bytes: a remapped copy.
+template <bool NT>
+__global__ __launch_bounds__(kBlock) void reorder_vec_kernel(
+    u32x4* __restrict__ dst, PtrTable src, size_t shard_vecs, size_t n_valid_bytes, int k)
+{
+    const size_t g = blockIdx.y;
+    const size_t chunk_begin = g * shard_vecs * 16;
+    if (chunk_begin >= n_valid_bytes) return;
+    size_t valid = n_valid_bytes - chunk_begin;
+    if (valid > shard_vecs * 16) valid = shard_vecs * 16;
+    const size_t nfull = valid / 16;
+    const size_t j = g / (size_t)k, l = g % (size_t)k;
+    const u32x4* __restrict__ s = (const u32x4*)src.ptr[l] + j * shard_vecs;
+    u32x4* __restrict__ d = dst + g * shard_vecs;
+
+    const size_t stride = (size_t)gridDim.x * kBlock;
+    size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    for (; i + 3 * stride < nfull; i += 4 * stride) {   // four loads in flight per lane
+        u32x4 a = ld<NT>(s + i), b = ld<NT>(s + i + stride);
+        u32x4 c = ld<NT>(s + i + 2 * stride), e = ld<NT>(s + i + 3 * stride);
+        st<NT>(d + i, a); st<NT>(d + i + stride, b);
+        st<NT>(d + i + 2 * stride, c); st<NT>(d + i + 3 * stride, e);
+    }
+    for (; i < nfull; i += stride) st<NT>(d + i, ld<NT>(s + i));
+
+    // ragged end of the logical buffer: fewer than 16 valid bytes remain
+    const size_t tail_halves = (valid - nfull * 16) / 2;
+    if (blockIdx.x == 0 && threadIdx.x < tail_halves) {
+        const uint16_t* sh = (const uint16_t*)(s + nfull);
+        uint16_t* dh = (uint16_t*)(d + nfull);
+        dh[threadIdx.x] = sh[threadIdx.x];
+    }
+}
+
+// General case: source and destination of a chunk sit at different offsets
+// within their 16-byte lines (odd shard sizes, sub-buffers that start anywhere
+// on an element boundary).  A workgroup stages the source bytes of one
+// destination tile in LDS with aligned 128-bit loads, then every lane rebuilds
+// its aligned 128-bit destination vector from two LDS vectors shifted by the
+// (workgroup-uniform) phase.  The partial vectors at the two ends of a chunk
+// are moved in 2-byte units.  Global memory is touched only inside the chunk.
+constexpr int kStageVecsPerThread = 4;
+constexpr int kTileVecs = kBlock * kStageVecsPerThread;   // destination vectors per tile
+constexpr int kTileBytes = kTileVecs * 16;
+
+__global__ __launch_bounds__(kBlock) void reorder_lds_kernel(
+    unsigned char* __restrict__ dst, PtrTable src, size_t shard_bytes, size_t n_valid_bytes, int k)
+{
+    __shared__ u32x4 stage[kTileVecs + 2];
+    const size_t g = blockIdx.y;
+    const size_t chunk_begin = g * shard_bytes;
+    if (chunk_begin >= n_valid_bytes) return;
+    size_t valid = n_valid_bytes - chunk_begin;
+    if (valid > shard_bytes) valid = shard_bytes;
+    const size_t j = g / (size_t)k, l = g % (size_t)k;
+
+    const uintptr_t d_lo = (uintptr_t)dst + chunk_begin;              // chunk in dst
+    const uintptr_t d_hi = d_lo + valid;
+    const uintptr_t s_chunk = (uintptr_t)src.ptr[l] + j * shard_bytes;  // chunk in src
+    const uintptr_t grid0 = d_lo & ~(uintptr_t)15;                     // 16-byte grid of dst
+    const size_t ntiles = (d_hi - grid0 + kTileBytes - 1) / kTileBytes;
+    const unsigned phase = (unsigned)((s_chunk - d_lo) & 15);           // even, uniform
+    const unsigned dshift = phase >> 2, half = (phase >> 1) & 1;
+    const uint16_t* stage_h = (const uint16_t*)stage;
+
+    for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const uintptr_t tile0 = grid0 + tile * kTileBytes;
+        const uintptr_t t_lo = tile0 > d_lo ? tile0 : d_lo;
+        const uintptr_t t_hi = tile0 + kTileBytes < d_hi ? tile0 + kTileBytes : d_hi;
+        const uintptr_t s_lo = s_chunk + (t_lo - d_lo), s_hi = s_chunk + (t_hi - d_lo);
+        const uintptr_t sa = s_lo & ~(uintptr_t)15;
+        const unsigned nsv = (unsigned)(((s_hi + 15) & ~(uintptr_t)15) - sa) / 16;   // <= kTileVecs+1
+
+        for (unsigned v = threadIdx.x; v < nsv; v += kBlock) {
+            const uintptr_t a = sa + (uintptr_t)v * 16;
+            if (a >= s_lo && a + 16 <= s_hi) {
+                stage[v] = *(const u32x4*)a;
+            } else {
+                uint16_t* row = (uint16_t*)&stage[v];
+                for (unsigned h = 0; h < 8; ++h) {
+                    const uintptr_t b = a + 2 * h;
+                    if (b >= s_lo && b < s_hi) row[h] = *(const uint16_t*)b;
+                }
+            }
+        }
+        __syncthreads();
+
+        for (unsigned vv = threadIdx.x; vv < kTileVecs; vv += kBlock) {
+            const uintptr_t a = tile0 + (uintptr_t)vv * 16;      // aligned dst address
+            if (a + 16 <= t_lo || a >= t_hi) continue;
+            // byte offset of this vector's source bytes inside the staged range
+            const long o = (long)(a - d_lo) + (long)(s_chunk - sa);   // a may lie below d_lo
+            if (a >= t_lo && a + 16 <= t_hi) {
+                const unsigned o16 = (unsigned)o >> 4;
+                const u32x4 lo = stage[o16], hi = stage[o16 + 1];
+                // shift the 8 staged dwords down by `dshift` dwords (uniform), then by
+                // half a dword if the phase is an odd number of 2-byte units
+                uint32_t w0 = lo.x, w1 = lo.y, w2 = lo.z, w3 = lo.w;
+                uint32_t w4 = hi.x, w5 = hi.y, w6 = hi.z, w7 = hi.w;
+                if (dshift & 1) { w0 = w1; w1 = w2; w2 = w3; w3 = w4; w4 = w5; w5 = w6; w6 = w7; }
+                if (dshift & 2) { w0 = w2; w1 = w3; w2 = w4; w3 = w5; w4 = w6; }
+                u32x4 out = {w0, w1, w2, w3};
+                if (half) {
+                    out.x = (w0 >> 16) | (w1 << 16);
+                    out.y = (w1 >> 16) | (w2 << 16);
+                    out.z = (w2 >> 16) | (w3 << 16);
+                    out.w = (w3 >> 16) | (w4 << 16);
+                }
+                *(u32x4*)a = out;
+            } else {
+                for (unsigned h = 0; h < 8; ++h) {
+                    const uintptr_t b = a + 2 * h;
+                    if (b >= t_lo && b < t_hi) *(uint16_t*)b = stage_h[(o + 2 * (long)h) >> 1];
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Step 2a: reduction of the partition-group reduce-scatter, accumulated over
+// micro-steps (Section 3.4).  One lane owns 8 consecutive elements: one
+// 128-bit load per rank buffer, all issued before the first addition.
+// ---------------------------------------------------------------------------
+
+template <bool ACCUM>
+__device__ __forceinline__ float rsa_element(const PtrTable& g, int p, size_t x, float before)
+{
+    float partial = bf16_one(((const uint16_t*)g.ptr[0])[x]);
+    for (int q = 1; q < p; ++q) partial = partial + bf16_one(((const uint16_t*)g.ptr[q])[x]);
+    return (ACCUM ? before : 0.0f) + partial;
+}
+
+template <int P, bool ACCUM, bool NT>
+__global__ __launch_bounds__(kBlock) void rsa_vec_kernel(
+    float* __restrict__ acc, SmallTable<P> g, size_t nvec)
+{
+    const size_t stride = (size_t)gridDim.x * kBlock;
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < nvec; i += stride) {
+        u32x4 v[P];
+        #pragma unroll
+        for (int q = 0; q < P; ++q) v[q] = ld<NT>((const u32x4*)g.ptr[q] + i);
+        f32x4 a0 = {0.0f, 0.0f, 0.0f, 0.0f}, a1 = a0;
+        if (ACCUM) {
+            a0 = ld<NT>((const f32x4*)acc + 2 * i);
+            a1 = ld<NT>((const f32x4*)acc + 2 * i + 1);
+        }
+        float s[8];
+        #pragma unroll
+        for (int e = 0; e < 4; ++e) { s[2 * e] = bf16_lo(v[0][e]); s[2 * e + 1] = bf16_hi(v[0][e]); }
+        #pragma unroll
+        for (int q = 1; q < P; ++q) {
+            #pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                s[2 * e] = s[2 * e] + bf16_lo(v[q][e]);
+                s[2 * e + 1] = s[2 * e + 1] + bf16_hi(v[q][e]);
+            }
+        }
+        f32x4 o0 = {a0.x + s[0], a0.y + s[1], a0.z + s[2], a0.w + s[3]};
+        f32x4 o1 = {a1.x + s[4], a1.y + s[5], a1.z + s[6], a1.w + s[7]};
+        st<NT>((f32x4*)acc + 2 * i, o0);
+        st<NT>((f32x4*)acc + 2 * i + 1, o1);
+    }
+}
+
+// Any p: rank buffers are consumed in batches of 8 loads, still in ascending
+// rank order.
+template <bool ACCUM, bool NT>
+__global__ __launch_bounds__(kBlock) void rsa_vec_anyp_kernel(
+    float* __restrict__ acc, PtrTable g, int p, size_t nvec)
+{
+    constexpr int B = 8;
+    const size_t stride = (size_t)gridDim.x * kBlock;
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < nvec; i += stride) {
+        f32x4 a0 = {0.0f, 0.0f, 0.0f, 0.0f}, a1 = a0;
+        if (ACCUM) {
+            a0 = ld<NT>((const f32x4*)acc + 2 * i);
+            a1 = ld<NT>((const f32x4*)acc + 2 * i + 1);
+        }
+        float s[8];
+        {
+            u32x4 first = ld<NT>((const u32x4*)g.ptr[0] + i);
+            #pragma unroll
+            for (int e = 0; e < 4; ++e) { s[2 * e] = bf16_lo(first[e]); s[2 * e + 1] = bf16_hi(first[e]); }
+        }
+        for (int q0 = 1; q0 < p; q0 += B) {
+            u32x4 v[B];
+            #pragma unroll
+            for (int b = 0; b < B; ++b)
+                if (q0 + b < p) v[b] = ld<NT>((const u32x4*)g.ptr[q0 + b] + i);
+            #pragma unroll
+            for (int b = 0; b < B; ++b) {
+                if (q0 + b < p) {
+                    #pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        s[2 * e] = s[2 * e] + bf16_lo(v[b][e]);
+                        s[2 * e + 1] = s[2 * e + 1] + bf16_hi(v[b][e]);
+                    }
+                }
+            }
+        }
+        f32x4 o0 = {a0.x + s[0], a0.y + s[1], a0.z + s[2], a0.w + s[3]};
+        f32x4 o1 = {a1.x + s[4], a1.y + s[5], a1.z + s[6], a1.w + s[7]};
+        st<NT>((f32x4*)acc + 2 * i, o0);
+        st<NT>((f32x4*)acc + 2 * i + 1, o1);
+    }
+}
+
+// One element per lane: the tail of the vector kernels (elements [first, count))
+// and the whole range when some buffer is not 16-byte aligned.
+template <bool ACCUM>
+__global__ __launch_bounds__(kBlock) void rsa_scalar_kernel(
+    float* __restrict__ acc, PtrTable g, int p, size_t first, size_t count)
+{
+    const size_t stride = (size_t)gridDim.x * kBlock;
+    for (size_t x = first + (size_t)blockIdx.x * kBlock + threadIdx.x; x < count; x += stride)
+        acc[x] = rsa_element<ACCUM>(g, p, x, ACCUM ? acc[x] : 0.0f);
+}
+
+// ---------------------------------------------------------------------------
+// Step 2b: reduction of the replication-group all-reduce at the accumulation
+// boundary and the scaling to a mean (Section 3.4).  One lane owns 4 elements
+// per copy.  `out` may be copies[0]: a lane reads its elements of every copy
+// before it writes them, and no other lane touches them.
+// ---------------------------------------------------------------------------
+
+template <int R, bool NT>
+__global__ __launch_bounds__(kBlock) void avg_vec_kernel(
+    float* out, SmallTable<R> a, float scale, size_t nvec)
+{
+    const size_t stride = (size_t)gridDim.x * kBlock;
+    size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    for (; i + stride < nvec; i += 2 * stride) {    // two vectors per copy in flight
+        f32x4 v[R], u[R];
+        #pragma unroll
+        for (int c = 0; c < R; ++c) {
+            v[c] = ld<NT>((const f32x4*)a.ptr[c] + i);
+            u[c] = ld<NT>((const f32x4*)a.ptr[c] + i + stride);
+        }
+        f32x4 sv = v[0], su = u[0];
+        #pragma unroll
+        for (int c = 1; c < R; ++c) { sv = sv + v[c]; su = su + u[c]; }
+        st<NT>((f32x4*)out + i, sv * scale);
+        st<NT>((f32x4*)out + i + stride, su * scale);
+    }
+    for (; i < nvec; i += stride) {
+        f32x4 v[R];
+        #pragma unroll
+        for (int c = 0; c < R; ++c) v[c] = ld<NT>((const f32x4*)a.ptr[c] + i);
+        f32x4 sv = v[0];
+        #pragma unroll
+        for (int c = 1; c < R; ++c) sv = sv + v[c];
+        st<NT>((f32x4*)out + i, sv * scale);
+    }
+}
+
+template <bool NT>
+__global__ __launch_bounds__(kBlock) void avg_vec_anyr_kernel(
+    float* out, PtrTable a, int r, float scale, size_t nvec)
+{
+    constexpr int B = 8;
+    const size_t stride = (size_t)gridDim.x * kBlock;
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < nvec; i += stride) {
+        f32x4 sum = ld<NT>((const f32x4*)a.ptr[0] + i);
+        for (int c0 = 1; c0 < r; c0 += B) {
+            f32x4 v[B];
+            #pragma unroll
+            for (int b = 0; b < B; ++b)
+                if (c0 + b < r) v[b] = ld<NT>((const f32x4*)a.ptr[c0 + b] + i);
+            #pragma unroll
+            for (int b = 0; b < B; ++b)
+                if (c0 + b < r) sum = sum + v[b];
+        }
+        st<NT>((f32x4*)out + i, sum * scale);
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void avg_scalar_kernel(
+    float* out, PtrTable a, int r, float scale, size_t first, size_t count)
+{
+    const size_t stride = (size_t)gridDim.x * kBlock;
+    for (size_t x = first + (size_t)blockIdx.x * kBlock + threadIdx.x; x < count; x += stride) {
+        float sum = ((const float*)a.ptr[0])[x];
+        for (int c = 1; c < r; ++c) sum = sum + ((const float*)a.ptr[c])[x];
+        out[x] = sum * scale;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Step 3: mixed-precision Adam on the shard (Sections 2.1, 3.2).  One fp32
+// operation per line; the order is part of the contract.
+// ---------------------------------------------------------------------------
+
+__device__ __forceinline__ void adam_element(float& w, float& m, float& v, float g,
+                                             const AdamScalars& hp)
+{
+    const float t1 = hp.beta1 * m;
+    const float t2 = hp.one_minus_beta1 * g;
+    const float m_new = t1 + t2;
+    const float gg = g * g;
+    const float t3 = hp.beta2 * v;
+    const float t4 = hp.one_minus_beta2 * gg;
+    const float v_new = t3 + t4;
+    const float m_hat = m_new / hp.bias_corr1;        // correctly rounded (build flag)
+    const float v_hat = v_new / hp.bias_corr2;
+    const float root = __builtin_sqrtf(v_hat);       // correctly rounded (build flag)
+    const float denom = root + hp.eps;
+    const float ratio = m_hat / denom;
+    const float decay = hp.weight_decay * w;
+    const float update = ratio + decay;
+    const float delta = hp.lr * update;
+    w = w - delta;
+    m = m_new;
+    v = v_new;
+}
+
+// One lane owns 8 consecutive elements: eight 128-bit loads in flight, seven
+// 128-bit stores (the bf16 parameter vector is exactly 16 bytes).
+template <bool BF16, bool NT>
+__global__ __launch_bounds__(kBlock) void adam_vec_kernel(
+    float* __restrict__ master, float* __restrict__ exp_avg, float* __restrict__ exp_avg_sq,
+    uint16_t* __restrict__ param_bf16, const float* __restrict__ grad, size_t nvec, AdamScalars hp)
+{
+    const size_t stride = (size_t)gridDim.x * kBlock;
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < nvec; i += stride) {
+        f32x4 g[2], w[2], m[2], v[2];
+        #pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            g[h] = ld<NT>((const f32x4*)grad + 2 * i + h);
+            w[h] = ld<NT>((const f32x4*)master + 2 * i + h);
+            m[h] = ld<NT>((const f32x4*)exp_avg + 2 * i + h);
+            v[h] = ld<NT>((const f32x4*)exp_avg_sq + 2 * i + h);
+        }
+        #pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            #pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float we = w[h][e], me = m[h][e], ve = v[h][e];
+                adam_element(we, me, ve, g[h][e], hp);
+                w[h][e] = we; m[h][e] = me; v[h][e] = ve;
+            }
+        }
+        #pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            st<NT>((f32x4*)master + 2 * i + h, w[h]);
+            st<NT>((f32x4*)exp_avg + 2 * i + h, m[h]);
+            st<NT>((f32x4*)exp_avg_sq + 2 * i + h, v[h]);
+        }
+        if (BF16) {
+            u32x4 b = {bf16_pack(w[0].x, w[0].y), bf16_pack(w[0].z, w[0].w),
+                       bf16_pack(w[1].x, w[1].y), bf16_pack(w[1].z, w[1].w)};
+            st<NT>((u32x4*)param_bf16 + i, b);
+        }
+    }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kBlock) void adam_scalar_kernel(
+    float* __restrict__ master, float* __restrict__ exp_avg, float* __restrict__ exp_avg_sq,
+    uint16_t* __restrict__ param_bf16, const float* __restrict__ grad, size_t first, size_t count,
+    AdamScalars hp)
+{
+    const size_t stride = (size_t)gridDim.x * kBlock;
+    for (size_t x = first + (size_t)blockIdx.x * kBlock + threadIdx.x; x < count; x += stride) {
+        float w = master[x], m = exp_avg[x], v = exp_avg_sq[x];
+        adam_element(w, m, v, grad[x], hp);
+        master[x] = w; exp_avg[x] = m; exp_avg_sq[x] = v;
+        if (BF16) param_bf16[x] = bf16_single(w);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Launch helpers
+// ---------------------------------------------------------------------------
+
+std::atomic<int> g_blocks_per_cu{0};
+constexpr int kDefaultBlocksPerCu = 8;
+
+int compute_units(int* out)
+{
+    static std::atomic<int> cached[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    if (dev >= 0 && dev < 64 && cached[dev].load() > 0) { *out = cached[dev].load(); return 0; }
+    int n = 0;
+    e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return (int)e;
+    if (n < 1) n = 1;
+    if (dev >= 0 && dev < 64) cached[dev].store(n);
+    *out = n;
+    return 0;
+}
+
+// Workgroups for `items` lane-sized work items: enough to cover them, at most
+// blocks_per_cu per compute unit (the kernels stride over the rest).
+int grid_for(size_t items, unsigned* blocks)
+{
+    int cus = 0;
+    if (int e = compute_units(&cus)) return e;
+    int per = g_blocks_per_cu.load();
+    if (per <= 0) per = kDefaultBlocksPerCu;
+    size_t want = (items + kBlock - 1) / kBlock;
+    size_t cap = (size_t)cus * (size_t)per;
+    if (want > cap) want = cap;
+    if (want < 1) want = 1;
+    *blocks = (unsigned)want;
+    return 0;
+}
+
+inline int launch_status()
+{
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? 0 : (int)e;
+}
+
+template <int N>
+SmallTable<N> small(const PtrTable& t)
+{
+    SmallTable<N> s;
+    for (int i = 0; i < N; ++i) s.ptr[i] = t.ptr[i];
+    return s;
+}
+
+constexpr bool kNT = true;   // streamed once: non-temporal loads and stores
+
+template <int P>
+void rsa_launch_fixed(float* acc, const PtrTable& g, size_t nvec, bool accumulate, unsigned blocks,
+                      hipStream_t st)
+{
+    if (accumulate)
+        hipLaunchKernelGGL((rsa_vec_kernel<P, true, kNT>), dim3(blocks), dim3(kBlock), 0, st, acc,
+                           small<P>(g), nvec);
+    else
+        hipLaunchKernelGGL((rsa_vec_kernel<P, false, kNT>), dim3(blocks), dim3(kBlock), 0, st, acc,
+                           small<P>(g), nvec);
+}
+
+template <int R>
+void avg_launch_fixed(float* out, const PtrTable& a, float scale, size_t nvec, unsigned blocks,
+                      hipStream_t st)
+{
+    hipLaunchKernelGGL((avg_vec_kernel<R, kNT>), dim3(blocks), dim3(kBlock), 0, st, out, small<R>(a),
+                       scale, nvec);
+}
+
+}  // namespace
+
+void set_blocks_per_cu(int n) { g_blocks_per_cu.store(n); }
+
+const char* hip_error_text(int err) { return hipGetErrorString((hipError_t)err); }
+
+int launch_reorder(void* dst, const PtrTable& src, size_t n_valid_bytes, size_t shard_bytes, int p,
+                   int k, bool vec16, void* stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    unsigned total = 0;
+    if (vec16) {
+        // four vectors per lane and pass; spread the block budget over the p chunks
+        if (int e = grid_for(shard_bytes / 16 / 4 * (size_t)p + 1, &total)) return e;
+        unsigned bx = (total + (unsigned)p - 1) / (unsigned)p;
+        hipLaunchKernelGGL((reorder_vec_kernel<kNT>), dim3(bx, (unsigned)p), dim3(kBlock), 0, st,
+                           (u32x4*)dst, src, shard_bytes / 16, n_valid_bytes, k);
+    } else {
+        size_t tiles = (shard_bytes + 15 + kTileBytes - 1) / kTileBytes + 1;
+        if (int e = grid_for(tiles * (size_t)p * kBlock, &total)) return e;
+        unsigned bx = (total + (unsigned)p - 1) / (unsigned)p;
+        if (bx > tiles) bx = (unsigned)tiles;
+        hipLaunchKernelGGL(reorder_lds_kernel, dim3(bx, (unsigned)p), dim3(kBlock), 0, st,
+                           (unsigned char*)dst, src, shard_bytes, n_valid_bytes, k);
+    }
+    return launch_status();
+}
+
+int launch_reduce_scatter_accum(float* acc, const PtrTable& g, size_t count, int p, bool accumulate,
+                                bool vec16, void* stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const size_t nvec = vec16 ? count / 8 : 0;
+    unsigned blocks = 0;
+    if (nvec) {
+        if (int e = grid_for(nvec, &blocks)) return e;
+        switch (p) {
+            case 1: rsa_launch_fixed<1>(acc, g, nvec, accumulate, blocks, st); break;
+            case 2: rsa_launch_fixed<2>(acc, g, nvec, accumulate, blocks, st); break;
+            case 4: rsa_launch_fixed<4>(acc, g, nvec, accumulate, blocks, st); break;
+            case 8: rsa_launch_fixed<8>(acc, g, nvec, accumulate, blocks, st); break;
+            case 16: rsa_launch_fixed<16>(acc, g, nvec, accumulate, blocks, st); break;
+            default:
+                if (accumulate)
+                    hipLaunchKernelGGL((rsa_vec_anyp_kernel<true, kNT>), dim3(blocks), dim3(kBlock),
+                                       0, st, acc, g, p, nvec);
+                else
+                    hipLaunchKernelGGL((rsa_vec_anyp_kernel<false, kNT>), dim3(blocks), dim3(kBlock),
+                                       0, st, acc, g, p, nvec);
+        }
+        if (int e = launch_status()) return e;
+    }
+    const size_t first = nvec * 8;
+    if (first < count) {
+        if (int e = grid_for(count - first, &blocks)) return e;
+        if (accumulate)
+            hipLaunchKernelGGL(rsa_scalar_kernel<true>, dim3(blocks), dim3(kBlock), 0, st, acc, g, p,
+                               first, count);
+        else
+            hipLaunchKernelGGL(rsa_scalar_kernel<false>, dim3(blocks), dim3(kBlock), 0, st, acc, g, p,
+                               first, count);
+        if (int e = launch_status()) return e;
+    }
+    return 0;
+}
+
+int launch_replica_average(float* out, const PtrTable& a, size_t count, int r, float scale,
+                           bool vec16, void* stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const size_t nvec = vec16 ? count / 4 : 0;
+    unsigned blocks = 0;
+    if (nvec) {
+        if (int e = grid_for((nvec + 1) / 2, &blocks)) return e;
+        switch (r) {
+            case 1: avg_launch_fixed<1>(out, a, scale, nvec, blocks, st); break;
+            case 2: avg_launch_fixed<2>(out, a, scale, nvec, blocks, st); break;
+            case 4: avg_launch_fixed<4>(out, a, scale, nvec, blocks, st); break;
+            case 8: avg_launch_fixed<8>(out, a, scale, nvec, blocks, st); break;
+            default:
+                hipLaunchKernelGGL((avg_vec_anyr_kernel<kNT>), dim3(blocks), dim3(kBlock), 0, st, out,
+                                   a, r, scale, nvec);
+        }
+        if (int e = launch_status()) return e;
+    }
+    const size_t first = nvec * 4;
+    if (first < count) {
+        if (int e = grid_for(count - first, &blocks)) return e;
+        hipLaunchKernelGGL(avg_scalar_kernel, dim3(blocks), dim3(kBlock), 0, st, out, a, r, scale,
+                           first, count);
+        if (int e = launch_status()) return e;
+    }
+    return 0;
+}
+
+int launch_adam(float* master, float* exp_avg, float* exp_avg_sq, uint16_t* param_bf16,
+                const float* grad, size_t count, const AdamScalars& hp, bool vec16, void* stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const size_t nvec = vec16 ? count / 8 : 0;
+    unsigned blocks = 0;
+    if (nvec) {
+        if (int e = grid_for(nvec, &blocks)) return e;
+        if (param_bf16)
+            hipLaunchKernelGGL((adam_vec_kernel<true, kNT>), dim3(blocks), dim3(kBlock), 0, st, master,
+                               exp_avg, exp_avg_sq, param_bf16, grad, nvec, hp);
+        else
+            hipLaunchKernelGGL((adam_vec_kernel<false, kNT>), dim3(blocks), dim3(kBlock), 0, st,
+                               master, exp_avg, exp_avg_sq, param_bf16, grad, nvec, hp);
+        if (int e = launch_status()) return e;
+    }
+    const size_t first = nvec * 8;
+    if (first < count) {
+        if (int e = grid_for(count - first, &blocks)) return e;
+        if (param_bf16)
+            hipLaunchKernelGGL(adam_scalar_kernel<true>, dim3(blocks), dim3(kBlock), 0, st, master,
+                               exp_avg, exp_avg_sq, param_bf16, grad, first, count, hp);
+        else
+            hipLaunchKernelGGL(adam_scalar_kernel<false>, dim3(blocks), dim3(kBlock), 0, st, master,
+                               exp_avg, exp_avg_sq, param_bf16, grad, first, count, hp);
+        if (int e = launch_status()) return e;
+    }
+    return 0;
+}
+
+}  // namespace mics

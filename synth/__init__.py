@@ -157,9 +157,12 @@ def build_host(force: bool = True) -> str:
 def build_device(force: bool = True) -> str:
     if force or not os.path.exists(_DEV_LIB):
         tmp = _DEV_LIB + f".tmp{os.getpid()}"
-        subprocess.run(["/opt/rocm/bin/hipcc", "--offload-arch=gfx950", "-O3", "-shared", "-fPIC",
-                        "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-                        "-o", tmp, os.path.join(_CSRC, "synth_dev.hip")], check=True)
+        res = subprocess.run(["/opt/rocm/bin/hipcc", "--offload-arch=gfx950", "-O3", "-shared",
+                              "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                              "-o", tmp, os.path.join(_CSRC, "synth_dev.hip")],
+                             capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
         os.replace(tmp, _DEV_LIB)
     return _DEV_LIB
 
@@ -185,6 +188,7 @@ def _dev_lib():
     if _dev is None:
         if not os.path.exists(_DEV_LIB):
             raise RuntimeError(f"{_DEV_LIB} is not built; run __graft_entry__.build() first")
+        import torch  # noqa: F401  (its HIP runtime must be the one this library binds to)
         _dev = ctypes.CDLL(_DEV_LIB)
         _dev.synth_fill_device.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_size_t,
                                            ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p,

@@ -1,0 +1,113 @@
+"""The C ABI without a GPU: exported symbols match the header, and every argument error is
+reported by the host-side checks before any HIP call (fake device addresses are never
+dereferenced)."""
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "mics.h")
+
+mics = pytest.importorskip("paper_2205_00119_amd", reason="libmics.so is not built")
+
+A = 0x7F0000000000          # a 16-byte aligned pretend device address
+BUF = 1 << 24                # pretend buffers are spaced far apart
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return re.findall(r"\b(mics_\w+)\s*\(", text)
+
+
+def test_library_exports_every_declared_function():
+    names = declared_functions()
+    assert len(names) >= 8
+    for name in names:
+        assert hasattr(mics.lib, name), f"{name} declared in mics.h but not exported"
+    assert sorted(set(names)) == sorted(mics.EXPORTS)
+
+
+def test_version_and_shard_elems():
+    assert mics.mics_version() >= 100
+    assert mics.mics_shard_elems(805412864, 16, 8) == 50338304
+    assert mics.mics_shard_elems(314639347, 32, 8) == 9832480
+    assert mics.mics_shard_elems(314639365, 32, 1) == 9832481
+    assert mics.mics_shard_elems(10, 4, 8) == 8
+    assert mics.mics_shard_elems(0, 4, 8) == 0
+    assert mics.mics_shard_elems(10, 0, 8) == 0
+
+
+def expect(code, fragment, fn, *args, **kw):
+    with pytest.raises(mics.MicsError) as ei:
+        fn(*args, **kw)
+    assert ei.value.code == code, str(ei.value)
+    assert fragment in str(ei.value), str(ei.value)
+    assert fragment in mics.mics_last_error()
+
+
+def test_reorder_argument_errors():
+    f = mics.mics_hier_gather_reorder
+    T = [A + BUF * (i + 1) for i in range(8)]
+    expect(mics.MICS_ERR_INVALID_ARG, "not divisible", f, A, T[:3], 10, 10, 4, 3, 2, stream=0)
+    expect(mics.MICS_ERR_UNSUPPORTED, "elem_bytes", f, A, T[:2], 10, 10, 4, 2, 8, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "n_valid", f, A, T[:2], 41, 10, 4, 2, 2, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "p = 0", f, A, [], 0, 10, 0, 0, 2, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "p = 256", f, A, T[:2], 10, 10, 256, 2, 2, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "k = 8", f, A, T[:8], 10, 10, 4, 8, 2, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "dst_flat is NULL", f, None, T[:2], 10, 10, 4, 2, 2, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "stage1_bufs[1] is NULL", f, A, [T[0], None], 10, 10, 4, 2, 2, stream=0)
+    expect(mics.MICS_ERR_ALIGNMENT, "dst_flat", f, A + 1, T[:2], 10, 10, 4, 2, 2, stream=0)
+    expect(mics.MICS_ERR_ALIGNMENT, "stage1_bufs[0]", f, A, [T[0] + 2, T[1]], 10, 10, 4, 2, 4, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "overlaps", f, A, [A + 16, T[1]], 40, 10, 4, 2, 2, stream=0)
+    # nothing to do is not an error and needs no GPU
+    f(A, T[:2], 0, 10, 4, 2, 2, stream=0)
+
+
+def test_reduce_scatter_accum_argument_errors():
+    f = mics.mics_reduce_scatter_accum
+    G = [A + BUF * (i + 1) for i in range(4)]
+    expect(mics.MICS_ERR_INVALID_ARG, "p = 0", f, A, [], 0, 8, False, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "p = 129", f, A, [G[0]] * 129, 0, 8, False, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "acc is NULL", f, None, G, 0, 8, False, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "grads_bf16[2] is NULL", f, A, [G[0], G[1], None], 0, 8, False, stream=0)
+    expect(mics.MICS_ERR_ALIGNMENT, "acc", f, A + 2, G, 0, 8, False, stream=0)
+    expect(mics.MICS_ERR_ALIGNMENT, "grads_bf16[1]", f, A, [G[0], G[1] + 1], 0, 8, False, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "overlaps", f, A, [G[0], A - 32], 32, 64, False, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "overflows", f, A, G, 1 << 63, 1 << 63, False, stream=0)
+    f(A, G, 0, 0, False, stream=0)
+
+
+def test_replica_average_argument_errors():
+    f = mics.mics_replica_average
+    C = [A + BUF * (i + 1) for i in range(4)]
+    expect(mics.MICS_ERR_INVALID_ARG, "r = 0", f, A, [], 8, 1.0, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "out is NULL", f, None, C, 8, 1.0, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "acc_copies[1] is NULL", f, A, [C[0], None], 8, 1.0, stream=0)
+    expect(mics.MICS_ERR_ALIGNMENT, "acc_copies[0]", f, A, [C[0] + 2], 8, 1.0, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "overlaps acc_copies[1]", f, A, [C[0], A], 8, 1.0, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "overlaps acc_copies[0]", f, A, [A + 16, C[1]], 8, 1.0, stream=0)
+    f(A, C, 0, 1.0, stream=0)
+
+
+def test_adam_argument_errors():
+    f = mics.mics_adam_shard
+    w, m, v, g, pb = (A + BUF * i for i in range(5))
+    hp = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0)
+    expect(mics.MICS_ERR_INVALID_ARG, "step = 0", f, w, m, v, pb, g, 8, step=0, stream=0, **hp)
+    expect(mics.MICS_ERR_INVALID_ARG, "non-NULL", f, w, None, v, pb, g, 8, step=1, stream=0, **hp)
+    expect(mics.MICS_ERR_ALIGNMENT, "exp_avg_sq", f, w, m, v + 2, pb, g, 8, step=1, stream=0, **hp)
+    expect(mics.MICS_ERR_ALIGNMENT, "param_bf16", f, w, m, v, pb + 1, g, 8, step=1, stream=0, **hp)
+    expect(mics.MICS_ERR_INVALID_ARG, "master overlaps exp_avg", f, w, w + 16, v, pb, g, 8, step=1, stream=0, **hp)
+    expect(mics.MICS_ERR_INVALID_ARG, "param_bf16 overlaps grad", f, w, m, v, g + 8, g, 8, step=1, stream=0, **hp)
+    expect(mics.MICS_ERR_INVALID_ARG, "beta1", f, w, m, v, pb, g, 8, step=1, stream=0, **dict(hp, beta1=1.0))
+    f(w, m, v, pb, g, 0, step=1, stream=0, **hp)
+
+
+def test_launch_knob_range():
+    mics.mics_set_blocks_per_cu(0)
+    with pytest.raises(mics.MicsError):
+        mics.mics_set_blocks_per_cu(65)
+    with pytest.raises(mics.MicsError):
+        mics.mics_set_blocks_per_cu(-1)

@@ -1,0 +1,311 @@
+"""HIP library vs CPU oracle, element by element, through the C ABI (sizes the oracle finishes in
+seconds, spanning several tiles and ragged tails).  Bars: reorder bit-exact; fp32 reductions
+bit-exact (contract: rel. error <= 1e-5 with fixed order); Adam master/moments rel. error <= 1e-6
+and normally bit-equal to the strict-fp32 oracle variant; bf16 outputs within 1 ulp."""
+import numpy as np
+import pytest
+import torch
+
+from util import adam_rel_err, bf16_ulp_distance, reduction_rel_err
+
+pytestmark = pytest.mark.gpu
+
+mics = pytest.importorskip("paper_2205_00119_amd")
+from gpu_util import Guarded, upload  # noqa: E402
+
+HP = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0)
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    yield
+    torch.cuda.synchronize()
+
+
+def tagged(gen, seed, n, dtype):
+    tab = gen.normal_table(1.0, "bf16") if dtype == np.uint16 else gen.normal_table(1.0, "f32").view(np.uint32)
+    return gen.fill_host(gen.stream_key(seed, gen.ROLE_PARAM), 0, n, tab)
+
+
+# ---- step 1: hierarchical gather reorder ------------------------------------------------------
+
+REORDER_CASES = [
+    # p, k, S, elem_bytes, n_valid (None = p*S), skew of sources, skew of destination
+    (4, 2, 4096 + 8, 2, None, 0, 0),          # the paper's geometry, vector path
+    (4, 2, 3 * 16384 + 24, 2, -5, 0, 0),      # several passes per chunk, ragged end
+    (16, 8, 20000, 2, -20003, 0, 0),          # cfg-5 geometry; the last chunk has no valid element
+    (8, 8, 1024, 4, None, 0, 0),              # single node: plain concatenation
+    (8, 1, 1000, 4, -1, 0, 0),                # one device per node
+    (32, 8, 2056, 2, -13, 0, 0),              # cfg-4 geometry with 13 padded elements
+    (12, 4, 8, 2, None, 0, 0),                # chunks of one vector
+    (6, 3, 4099, 2, None, 0, 0),              # odd shard: LDS re-phasing path
+    (6, 3, 4099, 4, -7, 0, 0),
+    (4, 2, 70001, 2, -2, 0, 0),               # odd shard spanning several tiles
+    (4, 2, 4096, 2, None, 3, 0),              # aligned shard, sources off by 6 bytes
+    (4, 2, 4096, 2, None, 0, 5),              # destination off by 10 bytes
+    (16, 8, 777, 2, -100, 1, 7),              # everything misaligned
+    (16, 8, 5, 2, None, 1, 1),                # chunks smaller than a vector
+    (3, 3, 1, 2, None, 0, 0),
+    (1, 1, 12345, 4, None, 0, 0),
+    (128, 8, 264, 2, None, 0, 0),             # largest group
+]
+
+
+@pytest.mark.parametrize("p,k,S,eb,nv,sskew,dskew", REORDER_CASES)
+def test_hier_gather_reorder_is_bit_exact(orc, gen, p, k, S, eb, nv, sskew, dskew):
+    dtype = np.uint16 if eb == 2 else np.uint32
+    n_valid = p * S if nv is None else p * S + nv
+    shards = [tagged(gen, 100 + g, S, dtype) for g in range(p)]
+    T = [orc.stage1_gather(shards, k, l) for l in range(k)]
+    T_dev = [Guarded(t.size, dtype, skew=sskew, fill=t) for t in T]
+    dst = Guarded(p * S, dtype, skew=dskew)
+    before = dst.numpy().copy()
+    mics.mics_hier_gather_reorder(dst.t, [t.t for t in T_dev], n_valid, S, p, k, eb)
+    torch.cuda.synchronize()
+    got = dst.numpy()
+    want = orc.concat_shards(shards, n_valid)
+    assert np.array_equal(got[:n_valid], want)
+    assert np.array_equal(got[:n_valid], orc.hier_gather_reorder(T, n_valid, S, p))
+    assert np.array_equal(got[n_valid:], before[n_valid:]), "wrote beyond n_valid"
+    assert dst.guards_intact() and all(t.guards_intact() for t in T_dev)
+
+
+def test_reorder_accepts_one_contiguous_gathered_buffer(orc, gen):
+    # the wrongly ordered result of a direct intra-node gather, W = [T_0 .. T_{k-1}], as input
+    p, k, S = 16, 8, 6152
+    shards = [tagged(gen, 200 + g, S, np.uint16) for g in range(p)]
+    T = [orc.stage1_gather(shards, k, l) for l in range(k)]
+    W = upload(orc.naive_intra_gather(T, p))
+    per = (p // k) * S
+    views = [W[l * per:(l + 1) * per] for l in range(k)]
+    dst = Guarded(p * S, np.uint16)
+    mics.mics_hier_gather_reorder(dst.t, views, p * S, S, p, k, 2)
+    torch.cuda.synchronize()
+    assert np.array_equal(dst.numpy(), np.concatenate(shards))
+    assert dst.guards_intact()
+
+
+# ---- step 2a: reduce-scatter + accumulate -------------------------------------------------------
+
+RSA_CASES = [
+    # p, total elements per rank buffer, elem_offset, count, micro-steps, skew
+    (1, 5000, 0, 5000, 2, 0),
+    (2, 40000, 0, 40000, 3, 0),
+    (4, 4 * 4104, 4104, 4104, 2, 0),          # rank view of rank 1
+    (4, 4 * 4104, 0, 4 * 4104, 2, 0),         # group view
+    (8, 70000, 8, 69987, 2, 0),               # ragged tail after the vectors
+    (16, 3 * 2048 * 8 + 40, 0, 3 * 2048 * 8 + 40, 3, 0),   # cfg-5 group size
+    (16, 50000, 1000, 3, 1, 0),               # fewer elements than one vector
+    (3, 30000, 0, 30000, 2, 0),               # p without an unrolled kernel
+    (5, 30000, 16, 20001, 2, 0),
+    (32, 20000, 160, 15000, 2, 0),            # cfg-4 group size
+    (128, 4096, 0, 4096, 1, 0),               # largest group
+    (4, 30000, 3, 20000, 2, 0),               # offset not a multiple of 8: element path
+    (8, 30000, 0, 30000, 2, 1),               # buffers off 16-byte alignment: element path
+]
+
+
+@pytest.mark.parametrize("p,total,off,count,steps,skew", RSA_CASES)
+def test_reduce_scatter_accum_matches_oracle_bit_for_bit(orc, gen, p, total, off, count, steps, skew):
+    tab = gen.normal_table(1e-3, "bf16")
+    out_tab = gen.normal_table(1e-1, "bf16")
+    acc = Guarded(count, np.float32, skew=skew)          # starts as canary garbage: must be overwritten
+    ref = np.full(count, np.nan, np.float32)
+    ref64 = np.zeros(count, np.float64)
+    abs_sum = np.zeros(count, np.float64)
+    for t in range(steps):
+        host = [gen.fill_host(gen.stream_key(300, gen.ROLE_GRAD, 0, t, q), 0, total, tab, out_tab, 0.01)
+                for q in range(p)]
+        dev = [Guarded(total, np.uint16, skew=skew, fill=h) for h in host]
+        mics.mics_reduce_scatter_accum(acc.t, [d.t for d in dev], off, count, t > 0)
+        torch.cuda.synchronize()
+        orc.reduce_scatter_accum(ref, host, off, t > 0)
+        orc.reduce_scatter_accum(ref64, host, off, t > 0, f64=True)
+        abs_sum += sum(np.abs(orc.bf16_widen(h[off:off + count]).astype(np.float64)) for h in host)
+        assert all(d.guards_intact() for d in dev)
+    got = acc.numpy()
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+    assert reduction_rel_err(got, ref64, abs_sum).max() <= 1e-5
+    assert acc.guards_intact()
+
+
+def test_reduce_scatter_accum_keeps_the_stated_order_and_zero_sign(orc):
+    one, tiny, nz = 0x3F80, 0x3380, 0x8000            # bf16 bits of 1, 2^-24, -0
+    n = 4096
+    def col(bits):
+        return np.full(n, bits, np.uint16)
+    for bufs, accumulate, start in [([col(one), col(tiny), col(tiny)], False, 0.0),
+                                    ([col(tiny), col(tiny), col(one)], False, 0.0),
+                                    ([col(tiny), col(tiny)], True, 1.0),
+                                    ([col(nz), col(nz)], False, 7.0)]:
+        acc = upload(np.full(n, start, np.float32))
+        ref = np.full(n, start, np.float32)
+        mics.mics_reduce_scatter_accum(acc, [upload(b) for b in bufs], 0, n, accumulate)
+        orc.reduce_scatter_accum(ref, bufs, 0, accumulate)
+        assert np.array_equal(acc.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+
+
+# ---- step 2b: replica average ----------------------------------------------------------------------
+
+@pytest.mark.parametrize("r,count,skew,alias", [
+    (1, 5000, 0, False), (2, 40000, 0, True), (4, 33333, 0, False), (8, 3 * 2048 * 8 + 5, 0, True),
+    (3, 20000, 0, False), (9, 20001, 0, True), (16, 9000, 0, False), (128, 2048, 0, False),
+    (4, 20000, 1, False), (8, 3, 0, False),
+])
+def test_replica_average_matches_oracle_bit_for_bit(orc, gen, r, count, skew, alias):
+    tab = gen.normal_table(3e-2, "f32")
+    host = [gen.fill_host(gen.stream_key(400, gen.ROLE_ACC, c), 0, count, tab) for c in range(r)]
+    dev = [Guarded(count, np.float32, skew=skew, fill=h) for h in host]
+    out = dev[0] if alias else Guarded(count, np.float32, skew=skew)
+    scale = float(np.float32(1.0 / (r * 16 * 12)))
+    mics.mics_replica_average(out.t, [d.t for d in dev], count, scale)
+    torch.cuda.synchronize()
+    want = orc.replica_average(host, scale)
+    assert np.array_equal(out.numpy().view(np.uint32), want.view(np.uint32))
+    assert out.guards_intact() and all(d.guards_intact() for d in dev)
+    for c in range(1, r):
+        assert np.array_equal(dev[c].numpy(), host[c]), "an input copy was modified"
+
+
+# ---- step 3: Adam -----------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("count,skew,want_bf16,wd,steps", [
+    (4096, 0, True, 0.0, 3), (3 * 2048 * 8 + 13, 0, True, 0.0, 2), (50001, 0, False, 0.01, 2),
+    (5, 0, True, 0.0, 1), (30000, 1, True, 0.1, 2), (77777, 0, True, 0.05, 4),
+])
+def test_adam_shard_matches_oracle(orc, gen, count, skew, want_bf16, wd, steps):
+    hp = dict(HP, weight_decay=wd)
+    w0 = gen.fill_host(gen.stream_key(500, gen.ROLE_MASTER), 0, count, gen.normal_table(0.02, "f32"))
+    gtab = gen.normal_table(2.6e-6, "f32")
+    w = Guarded(count, np.float32, skew=skew, fill=w0)
+    m = Guarded(count, np.float32, skew=skew, fill=np.zeros(count, np.float32))
+    v = Guarded(count, np.float32, skew=skew, fill=np.zeros(count, np.float32))
+    pb = Guarded(count, np.uint16, skew=skew) if want_bf16 else None
+    w64, m64, v64 = w0.copy(), np.zeros(count, np.float32), np.zeros(count, np.float32)
+    w32, m32, v32 = w0.copy(), np.zeros(count, np.float32), np.zeros(count, np.float32)
+    for t in range(1, steps + 1):
+        g_host = gen.fill_host(gen.stream_key(500, gen.ROLE_ACC, t), 0, count, gtab)
+        g = Guarded(count, np.float32, skew=skew, fill=g_host)
+        # both oracle variants step from the state the kernel steps from
+        w_prev = w.numpy().copy()
+        w64[:], m64[:], v64[:] = w_prev, m.numpy(), v.numpy()
+        w32[:], m32[:], v32[:] = w_prev, m.numpy(), v.numpy()
+        m_terms = 0.9 * np.abs(m64.astype(np.float64)) + 0.1 * np.abs(g_host.astype(np.float64))
+        mics.mics_adam_shard(w.t, m.t, v.t, pb.t if pb else None, g.t, count, step=t, **hp)
+        torch.cuda.synchronize()
+        pb64 = orc.adam_shard(w64, m64, v64, g_host, step=t, **hp)
+        pb32 = orc.adam_shard(w32, m32, v32, g_host, step=t, f32=True, **hp)
+        gw, gm, gv = w.numpy(), m.numpy(), v.numpy()
+        assert adam_rel_err(gw, w64, w_prev).max() <= 1e-6
+        assert (np.abs(gm.astype(np.float64) - m64) / np.maximum(m_terms, 1e-45)).max() <= 1e-6
+        assert (np.abs(gv.astype(np.float64) - v64) / np.maximum(np.abs(v64), 1e-45)).max() <= 1e-6
+        # same operations in the same order as the strict single-precision variant
+        assert np.array_equal(gw.view(np.uint32), w32.view(np.uint32))
+        assert np.array_equal(gm.view(np.uint32), m32.view(np.uint32))
+        assert np.array_equal(gv.view(np.uint32), v32.view(np.uint32))
+        if pb:
+            assert bf16_ulp_distance(pb.numpy(), pb64).max() <= 1
+            assert np.array_equal(pb.numpy(), pb32)
+        assert np.array_equal(g.numpy(), g_host) and g.guards_intact()
+    assert w.guards_intact() and m.guards_intact() and v.guards_intact()
+    assert pb is None or pb.guards_intact()
+
+
+def test_bf16_narrowing_of_arbitrary_masters(orc):
+    # lr = 0 and zero gradient/moments leave the master untouched, so param_bf16 = RNE(master)
+    # for every finite binary32 pattern we feed in, denormals and ties included
+    rng = np.random.default_rng(11)
+    u = rng.integers(0, 1 << 32, size=1 << 20, dtype=np.uint64).astype(np.uint32)
+    special = np.array([0x3F808000, 0x3F818000, 0x3F808001, 0x3F817FFF, 0x7F7FFFFF, 0x00000001,
+                        0x00008000, 0x00018000, 0x80000000, 0x007FFFFF, 0x00800000, 0xFF7FFFFF,
+                        0x0000FFFF, 0x7F7F8000, 0x7F7F7FFF], dtype=np.uint32)
+    u[:special.size] = special
+    f = u.view(np.float32)
+    f = f[np.isfinite(f)]
+    f = f[: (f.size // 8) * 8 + 3][: f.size]
+    n = f.size
+    w = upload(f.copy())
+    z = [upload(np.zeros(n, np.float32)) for _ in range(3)]
+    pb = torch.empty(n, dtype=torch.int16, device="cuda:0")
+    mics.mics_adam_shard(w, z[0], z[1], pb, z[2], n, lr=0.0, beta1=0.9, beta2=0.999, eps=1e-8,
+                         weight_decay=0.0, step=1)
+    torch.cuda.synchronize()
+    assert np.array_equal(w.cpu().numpy().view(np.uint32), f.view(np.uint32)), "fp32 denormals flushed?"
+    assert np.array_equal(pb.cpu().numpy().view(np.uint16), orc.bf16_narrow(f))
+
+
+def test_adam_handles_denormal_and_huge_inputs_like_the_oracle(orc):
+    g = np.array([1e-42, -3e-40, 0.0, 1e-30, 1e15, -1e18, 1e-20, 5e-39] * 16, np.float32)
+    n = g.size
+    w0 = np.linspace(-1, 1, n).astype(np.float32)
+    w, m, v = upload(w0.copy()), upload(np.zeros(n, np.float32)), upload(np.zeros(n, np.float32))
+    pb = torch.empty(n, dtype=torch.int16, device="cuda:0")
+    wr, mr, vr = w0.copy(), np.zeros(n, np.float32), np.zeros(n, np.float32)
+    for t in (1, 2):
+        mics.mics_adam_shard(w, m, v, pb, upload(g), n, step=t, **HP)
+        pbr = orc.adam_shard(wr, mr, vr, g, step=t, f32=True, **HP)
+    torch.cuda.synchronize()
+    assert np.array_equal(w.cpu().numpy().view(np.uint32), wr.view(np.uint32))
+    assert np.array_equal(m.cpu().numpy().view(np.uint32), mr.view(np.uint32))
+    assert np.array_equal(v.cpu().numpy().view(np.uint32), vr.view(np.uint32))
+    assert np.array_equal(pb.cpu().numpy().view(np.uint16), pbr)
+
+
+# ---- whole path on the smallest configuration ----------------------------------------------------------
+
+def test_tiny_config_pipeline_and_shard_gather_invariant(orc, gen):
+    cfg = gen.CONFIGS["tiny"]
+    p, k, r, s, S, N = cfg.p, cfg.k, cfg.r, cfg.s, cfg.S, cfg.N
+    n_pad = cfg.N_pad
+    gtab = gen.normal_table(cfg.sigma_grad, "bf16")
+    hp = dict(lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps, weight_decay=cfg.weight_decay)
+    scale = float(np.float32(1.0 / (r * p * s)))
+    w0 = gen.fill_host(gen.stream_key(cfg.seed, gen.ROLE_MASTER), 0, n_pad, gen.normal_table(0.02, "f32"))
+    grads = {(c, t, q): gen.fill_host(gen.stream_key(cfg.seed, gen.ROLE_GRAD, c, t, q), 0, n_pad, gtab)
+             for c in range(r) for t in range(s) for q in range(p)}
+    grads_dev = {key: upload(val) for key, val in grads.items()}
+
+    # oracle, group view
+    copies_ref = []
+    for c in range(r):
+        acc = np.empty(n_pad, np.float32)
+        for t in range(s):
+            orc.reduce_scatter_accum(acc, [grads[(c, t, q)] for q in range(p)], 0, t > 0)
+        copies_ref.append(acc)
+    avg_ref = orc.replica_average(copies_ref, scale)
+    w_ref, m_ref, v_ref = w0.copy(), np.zeros(n_pad, np.float32), np.zeros(n_pad, np.float32)
+    pb_ref = orc.adam_shard(w_ref, m_ref, v_ref, avg_ref, step=1, **hp)
+
+    # HIP, rank view: each simulated rank g owns [g*S, (g+1)*S)
+    shards_bf = []
+    w_all = np.empty(n_pad, np.float32)
+    for g in range(p):
+        copies = []
+        for c in range(r):
+            acc = torch.empty(S, dtype=torch.float32, device="cuda:0")
+            for t in range(s):
+                mics.mics_reduce_scatter_accum(acc, [grads_dev[(c, t, q)] for q in range(p)], g * S, S, t > 0)
+            copies.append(acc)
+        avg = torch.empty(S, dtype=torch.float32, device="cuda:0")
+        mics.mics_replica_average(avg, copies, S, scale)
+        sl = slice(g * S, (g + 1) * S)
+        assert np.array_equal(avg.cpu().numpy(), avg_ref[sl])
+        w = upload(w0[sl].copy())
+        m, v = torch.zeros_like(w), torch.zeros_like(w)
+        pb = torch.empty(S, dtype=torch.int16, device="cuda:0")
+        mics.mics_adam_shard(w, m, v, pb, avg, S, step=1, **hp)
+        shards_bf.append(pb)
+        w_all[sl] = w.cpu().numpy()
+    assert adam_rel_err(w_all, w_ref, w0).max() <= 1e-6
+
+    # next iteration's parameter gather: stage 1 (simulated inter-node all-gather: rank l's
+    # buffer receives the shards of ranks l, k+l, ...) then the HIP reorder
+    T = [torch.cat([shards_bf[j * k + l] for j in range(p // k)]) for l in range(k)]
+    flat = torch.empty(N, dtype=torch.int16, device="cuda:0")
+    mics.mics_hier_gather_reorder(flat, T, N, S, p, k, 2)
+    torch.cuda.synchronize()
+    got = flat.cpu().numpy().view(np.uint16)
+    assert bf16_ulp_distance(got, pb_ref[:N]).max() <= 1
+    # and exactly the bf16 rounding of the HIP master shards laid end to end
+    assert np.array_equal(got, orc.bf16_narrow(w_all)[:N])
