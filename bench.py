@@ -42,6 +42,10 @@ def parse_args():
     ap.add_argument("--rank", type=int, default=5, help="which group rank's shard is simulated")
     ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="before the steps, run one plain copy of known size (the reorder with "
+                         "p = k = 1 over the whole layer: N bf16 read, N bf16 written) so that "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE can be scaled against it")
     ap.add_argument("--cpu-sample", type=int, default=16 << 20,
                     help="shard elements the CPU oracle is timed on")
     return ap.parse_args()
@@ -148,6 +152,9 @@ def main():
             marks[4].record(stream)
             all_marks.append(marks)
 
+    if args.calibration_copy:
+        mics.mics_hier_gather_reorder(F, [W], N, N, 1, 1, 2, stream=sh)
+        torch.cuda.synchronize()
     for it in range(1, args.warmup + 1):
         step(it, False)
     torch.cuda.synchronize()

@@ -163,7 +163,7 @@ int mics_adam_shard(float* master, float* exp_avg, float* exp_avg_sq,
  * Launch-shape knob for measurements (not part of the method): sets how many
  * workgroups per compute unit the streaming kernels of later calls launch at
  * most; 0 restores the built-in choice.  Process-wide.  Returns MICS_OK or
- * MICS_ERR_INVALID_ARG (negative or > 64).
+ * MICS_ERR_INVALID_ARG (negative or > 4096).
  */
 int mics_set_blocks_per_cu(int blocks_per_cu);
 

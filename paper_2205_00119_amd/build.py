@@ -34,4 +34,7 @@ def build(extra_flags=(), out: str = LIB, verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+    # usage: build.py [out.so] [-DNAME=VALUE ...]   (variants for measurements)
+    out = next((a for a in sys.argv[1:] if not a.startswith("-")), LIB)
+    print(build([a for a in sys.argv[1:] if a.startswith("-")], out=out, verbose=True))

@@ -53,8 +53,8 @@ size_t mics_shard_elems(size_t n, int p, size_t align_elems)
 
 int mics_set_blocks_per_cu(int blocks_per_cu)
 {
-    if (blocks_per_cu < 0 || blocks_per_cu > 64)
-        return fail(MICS_ERR_INVALID_ARG, "mics_set_blocks_per_cu: %d not in [0, 64]", blocks_per_cu);
+    if (blocks_per_cu < 0 || blocks_per_cu > 4096)
+        return fail(MICS_ERR_INVALID_ARG, "mics_set_blocks_per_cu: %d not in [0, 4096]", blocks_per_cu);
     mics::set_blocks_per_cu(blocks_per_cu);
     return MICS_OK;
 }

@@ -28,7 +28,68 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kBlock = 256;
+// Launch shape and cache hints per kernel family; the defaults are the measured best on
+// MI355X for the h = 8192, p = 16 shard shapes.  *_BLOCK = workgroup size, *_BPC = cap on
+// workgroups per compute unit (a grid that covers the data with one pass per lane when the
+// cap is not reached; lanes stride over the rest), *_NTL / *_NTS = non-temporal loads / stores.
+#ifndef MICS_REORDER_BLOCK
+#define MICS_REORDER_BLOCK 256
+#endif
+#ifndef MICS_REORDER_BPC
+#define MICS_REORDER_BPC 16
+#endif
+#ifndef MICS_REORDER_NTL
+#define MICS_REORDER_NTL 1
+#endif
+#ifndef MICS_REORDER_NTS
+#define MICS_REORDER_NTS 1
+#endif
+#ifndef MICS_RSA_BLOCK
+#define MICS_RSA_BLOCK 1024
+#endif
+#ifndef MICS_RSA_BPC
+#define MICS_RSA_BPC 32
+#endif
+#ifndef MICS_RSA_NTL
+#define MICS_RSA_NTL 1
+#endif
+#ifndef MICS_RSA_NTS
+#define MICS_RSA_NTS 0
+#endif
+#ifndef MICS_AVG_BLOCK
+#define MICS_AVG_BLOCK 1024
+#endif
+#ifndef MICS_AVG_BPC
+#define MICS_AVG_BPC 32
+#endif
+#ifndef MICS_AVG_NTL
+#define MICS_AVG_NTL 1
+#endif
+#ifndef MICS_AVG_NTS
+#define MICS_AVG_NTS 0
+#endif
+#ifndef MICS_ADAM_BLOCK
+#define MICS_ADAM_BLOCK 1024
+#endif
+#ifndef MICS_ADAM_BPC
+#define MICS_ADAM_BPC 32
+#endif
+#ifndef MICS_ADAM_NTL
+#define MICS_ADAM_NTL 1
+#endif
+#ifndef MICS_ADAM_NTS
+#define MICS_ADAM_NTS 1
+#endif
+
+constexpr int kBlock = 256;              // element-wise (tail / unaligned) kernels, LDS reorder
+constexpr int kReorderBlock = MICS_REORDER_BLOCK;
+constexpr int kRsaBlock = MICS_RSA_BLOCK;
+constexpr int kAvgBlock = MICS_AVG_BLOCK;
+constexpr int kAdamBlock = MICS_ADAM_BLOCK;
+constexpr bool kReorderNtl = MICS_REORDER_NTL, kReorderNts = MICS_REORDER_NTS;
+constexpr bool kRsaNtl = MICS_RSA_NTL, kRsaNts = MICS_RSA_NTS;
+constexpr bool kAvgNtl = MICS_AVG_NTL, kAvgNts = MICS_AVG_NTS;
+constexpr bool kAdamNtl = MICS_ADAM_NTL, kAdamNts = MICS_ADAM_NTS;
 
 // Compile-time sized pointer table for the unrolled kernels (keeps the
 // kernel-argument segment small); the launcher copies out of PtrTable.
@@ -78,8 +139,7 @@ __device__ __forceinline__ uint16_t bf16_single(float a)
 // ---------------------------------------------------------------------------
 
 // All addresses and the shard size are multiples of 16 bytes: a remapped copy.
-template <bool NT>
-__global__ __launch_bounds__(kBlock) void reorder_vec_kernel(
+__global__ __launch_bounds__(kReorderBlock) void reorder_vec_kernel(
     u32x4* __restrict__ dst, PtrTable src, size_t shard_vecs, size_t n_valid_bytes, int k)
 {
     const size_t g = blockIdx.y;
@@ -92,15 +152,15 @@ __global__ __launch_bounds__(kBlock) void reorder_vec_kernel(
     const u32x4* __restrict__ s = (const u32x4*)src.ptr[l] + j * shard_vecs;
     u32x4* __restrict__ d = dst + g * shard_vecs;
 
-    const size_t stride = (size_t)gridDim.x * kBlock;
-    size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * kReorderBlock;
+    size_t i = (size_t)blockIdx.x * kReorderBlock + threadIdx.x;
     for (; i + 3 * stride < nfull; i += 4 * stride) {   // four loads in flight per lane
-        u32x4 a = ld<NT>(s + i), b = ld<NT>(s + i + stride);
-        u32x4 c = ld<NT>(s + i + 2 * stride), e = ld<NT>(s + i + 3 * stride);
-        st<NT>(d + i, a); st<NT>(d + i + stride, b);
-        st<NT>(d + i + 2 * stride, c); st<NT>(d + i + 3 * stride, e);
+        u32x4 a = ld<kReorderNtl>(s + i), b = ld<kReorderNtl>(s + i + stride);
+        u32x4 c = ld<kReorderNtl>(s + i + 2 * stride), e = ld<kReorderNtl>(s + i + 3 * stride);
+        st<kReorderNts>(d + i, a); st<kReorderNts>(d + i + stride, b);
+        st<kReorderNts>(d + i + 2 * stride, c); st<kReorderNts>(d + i + 3 * stride, e);
     }
-    for (; i < nfull; i += stride) st<NT>(d + i, ld<NT>(s + i));
+    for (; i < nfull; i += stride) st<kReorderNts>(d + i, ld<kReorderNtl>(s + i));
 
     // ragged end of the logical buffer: fewer than 16 valid bytes remain
     const size_t tail_halves = (valid - nfull * 16) / 2;
@@ -211,19 +271,19 @@ __device__ __forceinline__ float rsa_element(const PtrTable& g, int p, size_t x,
     return (ACCUM ? before : 0.0f) + partial;
 }
 
-template <int P, bool ACCUM, bool NT>
-__global__ __launch_bounds__(kBlock) void rsa_vec_kernel(
+template <int P, bool ACCUM>
+__global__ __launch_bounds__(kRsaBlock) void rsa_vec_kernel(
     float* __restrict__ acc, SmallTable<P> g, size_t nvec)
 {
-    const size_t stride = (size_t)gridDim.x * kBlock;
-    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < nvec; i += stride) {
+    const size_t stride = (size_t)gridDim.x * kRsaBlock;
+    for (size_t i = (size_t)blockIdx.x * kRsaBlock + threadIdx.x; i < nvec; i += stride) {
         u32x4 v[P];
         #pragma unroll
-        for (int q = 0; q < P; ++q) v[q] = ld<NT>((const u32x4*)g.ptr[q] + i);
+        for (int q = 0; q < P; ++q) v[q] = ld<kRsaNtl>((const u32x4*)g.ptr[q] + i);
         f32x4 a0 = {0.0f, 0.0f, 0.0f, 0.0f}, a1 = a0;
         if (ACCUM) {
-            a0 = ld<NT>((const f32x4*)acc + 2 * i);
-            a1 = ld<NT>((const f32x4*)acc + 2 * i + 1);
+            a0 = ld<kRsaNtl>((const f32x4*)acc + 2 * i);
+            a1 = ld<kRsaNtl>((const f32x4*)acc + 2 * i + 1);
         }
         float s[8];
         #pragma unroll
@@ -238,28 +298,28 @@ __global__ __launch_bounds__(kBlock) void rsa_vec_kernel(
         }
         f32x4 o0 = {a0.x + s[0], a0.y + s[1], a0.z + s[2], a0.w + s[3]};
         f32x4 o1 = {a1.x + s[4], a1.y + s[5], a1.z + s[6], a1.w + s[7]};
-        st<NT>((f32x4*)acc + 2 * i, o0);
-        st<NT>((f32x4*)acc + 2 * i + 1, o1);
+        st<kRsaNts>((f32x4*)acc + 2 * i, o0);
+        st<kRsaNts>((f32x4*)acc + 2 * i + 1, o1);
     }
 }
 
 // Any p: rank buffers are consumed in batches of 8 loads, still in ascending
 // rank order.
-template <bool ACCUM, bool NT>
-__global__ __launch_bounds__(kBlock) void rsa_vec_anyp_kernel(
+template <bool ACCUM>
+__global__ __launch_bounds__(kRsaBlock) void rsa_vec_anyp_kernel(
     float* __restrict__ acc, PtrTable g, int p, size_t nvec)
 {
     constexpr int B = 8;
-    const size_t stride = (size_t)gridDim.x * kBlock;
-    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < nvec; i += stride) {
+    const size_t stride = (size_t)gridDim.x * kRsaBlock;
+    for (size_t i = (size_t)blockIdx.x * kRsaBlock + threadIdx.x; i < nvec; i += stride) {
         f32x4 a0 = {0.0f, 0.0f, 0.0f, 0.0f}, a1 = a0;
         if (ACCUM) {
-            a0 = ld<NT>((const f32x4*)acc + 2 * i);
-            a1 = ld<NT>((const f32x4*)acc + 2 * i + 1);
+            a0 = ld<kRsaNtl>((const f32x4*)acc + 2 * i);
+            a1 = ld<kRsaNtl>((const f32x4*)acc + 2 * i + 1);
         }
         float s[8];
         {
-            u32x4 first = ld<NT>((const u32x4*)g.ptr[0] + i);
+            u32x4 first = ld<kRsaNtl>((const u32x4*)g.ptr[0] + i);
             #pragma unroll
             for (int e = 0; e < 4; ++e) { s[2 * e] = bf16_lo(first[e]); s[2 * e + 1] = bf16_hi(first[e]); }
         }
@@ -267,7 +327,7 @@ __global__ __launch_bounds__(kBlock) void rsa_vec_anyp_kernel(
             u32x4 v[B];
             #pragma unroll
             for (int b = 0; b < B; ++b)
-                if (q0 + b < p) v[b] = ld<NT>((const u32x4*)g.ptr[q0 + b] + i);
+                if (q0 + b < p) v[b] = ld<kRsaNtl>((const u32x4*)g.ptr[q0 + b] + i);
             #pragma unroll
             for (int b = 0; b < B; ++b) {
                 if (q0 + b < p) {
@@ -281,8 +341,8 @@ __global__ __launch_bounds__(kBlock) void rsa_vec_anyp_kernel(
         }
         f32x4 o0 = {a0.x + s[0], a0.y + s[1], a0.z + s[2], a0.w + s[3]};
         f32x4 o1 = {a1.x + s[4], a1.y + s[5], a1.z + s[6], a1.w + s[7]};
-        st<NT>((f32x4*)acc + 2 * i, o0);
-        st<NT>((f32x4*)acc + 2 * i + 1, o1);
+        st<kRsaNts>((f32x4*)acc + 2 * i, o0);
+        st<kRsaNts>((f32x4*)acc + 2 * i + 1, o1);
     }
 }
 
@@ -304,54 +364,53 @@ __global__ __launch_bounds__(kBlock) void rsa_scalar_kernel(
 // before it writes them, and no other lane touches them.
 // ---------------------------------------------------------------------------
 
-template <int R, bool NT>
-__global__ __launch_bounds__(kBlock) void avg_vec_kernel(
+template <int R>
+__global__ __launch_bounds__(kAvgBlock) void avg_vec_kernel(
     float* out, SmallTable<R> a, float scale, size_t nvec)
 {
-    const size_t stride = (size_t)gridDim.x * kBlock;
-    size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * kAvgBlock;
+    size_t i = (size_t)blockIdx.x * kAvgBlock + threadIdx.x;
     for (; i + stride < nvec; i += 2 * stride) {    // two vectors per copy in flight
         f32x4 v[R], u[R];
         #pragma unroll
         for (int c = 0; c < R; ++c) {
-            v[c] = ld<NT>((const f32x4*)a.ptr[c] + i);
-            u[c] = ld<NT>((const f32x4*)a.ptr[c] + i + stride);
+            v[c] = ld<kAvgNtl>((const f32x4*)a.ptr[c] + i);
+            u[c] = ld<kAvgNtl>((const f32x4*)a.ptr[c] + i + stride);
         }
         f32x4 sv = v[0], su = u[0];
         #pragma unroll
         for (int c = 1; c < R; ++c) { sv = sv + v[c]; su = su + u[c]; }
-        st<NT>((f32x4*)out + i, sv * scale);
-        st<NT>((f32x4*)out + i + stride, su * scale);
+        st<kAvgNts>((f32x4*)out + i, sv * scale);
+        st<kAvgNts>((f32x4*)out + i + stride, su * scale);
     }
     for (; i < nvec; i += stride) {
         f32x4 v[R];
         #pragma unroll
-        for (int c = 0; c < R; ++c) v[c] = ld<NT>((const f32x4*)a.ptr[c] + i);
+        for (int c = 0; c < R; ++c) v[c] = ld<kAvgNtl>((const f32x4*)a.ptr[c] + i);
         f32x4 sv = v[0];
         #pragma unroll
         for (int c = 1; c < R; ++c) sv = sv + v[c];
-        st<NT>((f32x4*)out + i, sv * scale);
+        st<kAvgNts>((f32x4*)out + i, sv * scale);
     }
 }
 
-template <bool NT>
-__global__ __launch_bounds__(kBlock) void avg_vec_anyr_kernel(
+__global__ __launch_bounds__(kAvgBlock) void avg_vec_anyr_kernel(
     float* out, PtrTable a, int r, float scale, size_t nvec)
 {
     constexpr int B = 8;
-    const size_t stride = (size_t)gridDim.x * kBlock;
-    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < nvec; i += stride) {
-        f32x4 sum = ld<NT>((const f32x4*)a.ptr[0] + i);
+    const size_t stride = (size_t)gridDim.x * kAvgBlock;
+    for (size_t i = (size_t)blockIdx.x * kAvgBlock + threadIdx.x; i < nvec; i += stride) {
+        f32x4 sum = ld<kAvgNtl>((const f32x4*)a.ptr[0] + i);
         for (int c0 = 1; c0 < r; c0 += B) {
             f32x4 v[B];
             #pragma unroll
             for (int b = 0; b < B; ++b)
-                if (c0 + b < r) v[b] = ld<NT>((const f32x4*)a.ptr[c0 + b] + i);
+                if (c0 + b < r) v[b] = ld<kAvgNtl>((const f32x4*)a.ptr[c0 + b] + i);
             #pragma unroll
             for (int b = 0; b < B; ++b)
                 if (c0 + b < r) sum = sum + v[b];
         }
-        st<NT>((f32x4*)out + i, sum * scale);
+        st<kAvgNts>((f32x4*)out + i, sum * scale);
     }
 }
 
@@ -394,42 +453,47 @@ __device__ __forceinline__ void adam_element(float& w, float& m, float& v, float
     v = v_new;
 }
 
-// One lane owns 8 consecutive elements: eight 128-bit loads in flight, seven
-// 128-bit stores (the bf16 parameter vector is exactly 16 bytes).
-template <bool BF16, bool NT>
-__global__ __launch_bounds__(kBlock) void adam_vec_kernel(
+// One lane owns two groups of 4 consecutive elements, a grid stride apart, so that every
+// load and store instruction of a wavefront covers one contiguous kilobyte (stores that
+// leave gaps between lanes reach memory as partial lines and cost extra traffic).
+// Eight 128-bit loads are in flight before the first use.
+template <bool BF16>
+__global__ __launch_bounds__(kAdamBlock) void adam_vec_kernel(
     float* __restrict__ master, float* __restrict__ exp_avg, float* __restrict__ exp_avg_sq,
     uint16_t* __restrict__ param_bf16, const float* __restrict__ grad, size_t nvec, AdamScalars hp)
 {
-    const size_t stride = (size_t)gridDim.x * kBlock;
-    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < nvec; i += stride) {
+    const size_t stride = (size_t)gridDim.x * kAdamBlock;
+    for (size_t i0 = (size_t)blockIdx.x * kAdamBlock + threadIdx.x; i0 < nvec; i0 += 2 * stride) {
+        const size_t i1 = i0 + stride;
+        const bool two = i1 < nvec;
         f32x4 g[2], w[2], m[2], v[2];
-        #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            g[h] = ld<NT>((const f32x4*)grad + 2 * i + h);
-            w[h] = ld<NT>((const f32x4*)master + 2 * i + h);
-            m[h] = ld<NT>((const f32x4*)exp_avg + 2 * i + h);
-            v[h] = ld<NT>((const f32x4*)exp_avg_sq + 2 * i + h);
+        g[0] = ld<kAdamNtl>((const f32x4*)grad + i0);
+        w[0] = ld<kAdamNtl>((const f32x4*)master + i0);
+        m[0] = ld<kAdamNtl>((const f32x4*)exp_avg + i0);
+        v[0] = ld<kAdamNtl>((const f32x4*)exp_avg_sq + i0);
+        if (two) {
+            g[1] = ld<kAdamNtl>((const f32x4*)grad + i1);
+            w[1] = ld<kAdamNtl>((const f32x4*)master + i1);
+            m[1] = ld<kAdamNtl>((const f32x4*)exp_avg + i1);
+            v[1] = ld<kAdamNtl>((const f32x4*)exp_avg_sq + i1);
         }
         #pragma unroll
         for (int h = 0; h < 2; ++h) {
+            if (h == 1 && !two) break;
             #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 float we = w[h][e], me = m[h][e], ve = v[h][e];
                 adam_element(we, me, ve, g[h][e], hp);
                 w[h][e] = we; m[h][e] = me; v[h][e] = ve;
             }
-        }
-        #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            st<NT>((f32x4*)master + 2 * i + h, w[h]);
-            st<NT>((f32x4*)exp_avg + 2 * i + h, m[h]);
-            st<NT>((f32x4*)exp_avg_sq + 2 * i + h, v[h]);
-        }
-        if (BF16) {
-            u32x4 b = {bf16_pack(w[0].x, w[0].y), bf16_pack(w[0].z, w[0].w),
-                       bf16_pack(w[1].x, w[1].y), bf16_pack(w[1].z, w[1].w)};
-            st<NT>((u32x4*)param_bf16 + i, b);
+            const size_t i = h ? i1 : i0;
+            st<kAdamNts>((f32x4*)master + i, w[h]);
+            st<kAdamNts>((f32x4*)exp_avg + i, m[h]);
+            st<kAdamNts>((f32x4*)exp_avg_sq + i, v[h]);
+            if (BF16) {
+                u32x2 b = {bf16_pack(w[h].x, w[h].y), bf16_pack(w[h].z, w[h].w)};
+                st<kAdamNts>((u32x2*)param_bf16 + i, b);
+            }
         }
     }
 }
@@ -454,7 +518,6 @@ __global__ __launch_bounds__(kBlock) void adam_scalar_kernel(
 // ---------------------------------------------------------------------------
 
 std::atomic<int> g_blocks_per_cu{0};
-constexpr int kDefaultBlocksPerCu = 8;
 
 int compute_units(int* out)
 {
@@ -472,21 +535,23 @@ int compute_units(int* out)
     return 0;
 }
 
-// Workgroups for `items` lane-sized work items: enough to cover them, at most
-// blocks_per_cu per compute unit (the kernels stride over the rest).
-int grid_for(size_t items, unsigned* blocks)
+// Workgroups of `block` lanes for `items` lane-sized work items: enough to cover them, at
+// most `bpc` per compute unit (the kernels stride over the rest).
+int grid_for(size_t items, int block, int bpc, unsigned* blocks)
 {
     int cus = 0;
     if (int e = compute_units(&cus)) return e;
-    int per = g_blocks_per_cu.load();
-    if (per <= 0) per = kDefaultBlocksPerCu;
-    size_t want = (items + kBlock - 1) / kBlock;
-    size_t cap = (size_t)cus * (size_t)per;
+    const int forced = g_blocks_per_cu.load();
+    if (forced > 0) bpc = forced;
+    size_t want = (items + (size_t)block - 1) / (size_t)block;
+    const size_t cap = (size_t)cus * (size_t)bpc;
     if (want > cap) want = cap;
     if (want < 1) want = 1;
     *blocks = (unsigned)want;
     return 0;
 }
+
+constexpr int kTailBpc = 8;
 
 inline int launch_status()
 {
@@ -502,17 +567,15 @@ SmallTable<N> small(const PtrTable& t)
     return s;
 }
 
-constexpr bool kNT = true;   // streamed once: non-temporal loads and stores
-
 template <int P>
 void rsa_launch_fixed(float* acc, const PtrTable& g, size_t nvec, bool accumulate, unsigned blocks,
                       hipStream_t st)
 {
     if (accumulate)
-        hipLaunchKernelGGL((rsa_vec_kernel<P, true, kNT>), dim3(blocks), dim3(kBlock), 0, st, acc,
+        hipLaunchKernelGGL((rsa_vec_kernel<P, true>), dim3(blocks), dim3(kRsaBlock), 0, st, acc,
                            small<P>(g), nvec);
     else
-        hipLaunchKernelGGL((rsa_vec_kernel<P, false, kNT>), dim3(blocks), dim3(kBlock), 0, st, acc,
+        hipLaunchKernelGGL((rsa_vec_kernel<P, false>), dim3(blocks), dim3(kRsaBlock), 0, st, acc,
                            small<P>(g), nvec);
 }
 
@@ -520,7 +583,7 @@ template <int R>
 void avg_launch_fixed(float* out, const PtrTable& a, float scale, size_t nvec, unsigned blocks,
                       hipStream_t st)
 {
-    hipLaunchKernelGGL((avg_vec_kernel<R, kNT>), dim3(blocks), dim3(kBlock), 0, st, out, small<R>(a),
+    hipLaunchKernelGGL((avg_vec_kernel<R>), dim3(blocks), dim3(kAvgBlock), 0, st, out, small<R>(a),
                        scale, nvec);
 }
 
@@ -537,13 +600,13 @@ int launch_reorder(void* dst, const PtrTable& src, size_t n_valid_bytes, size_t 
     unsigned total = 0;
     if (vec16) {
         // four vectors per lane and pass; spread the block budget over the p chunks
-        if (int e = grid_for(shard_bytes / 16 / 4 * (size_t)p + 1, &total)) return e;
+        if (int e = grid_for(shard_bytes / 16 / 4 * (size_t)p + 1, kReorderBlock, MICS_REORDER_BPC, &total)) return e;
         unsigned bx = (total + (unsigned)p - 1) / (unsigned)p;
-        hipLaunchKernelGGL((reorder_vec_kernel<kNT>), dim3(bx, (unsigned)p), dim3(kBlock), 0, st,
+        hipLaunchKernelGGL(reorder_vec_kernel, dim3(bx, (unsigned)p), dim3(kReorderBlock), 0, st,
                            (u32x4*)dst, src, shard_bytes / 16, n_valid_bytes, k);
     } else {
         size_t tiles = (shard_bytes + 15 + kTileBytes - 1) / kTileBytes + 1;
-        if (int e = grid_for(tiles * (size_t)p * kBlock, &total)) return e;
+        if (int e = grid_for(tiles * (size_t)p * kBlock, kBlock, MICS_REORDER_BPC, &total)) return e;
         unsigned bx = (total + (unsigned)p - 1) / (unsigned)p;
         if (bx > tiles) bx = (unsigned)tiles;
         hipLaunchKernelGGL(reorder_lds_kernel, dim3(bx, (unsigned)p), dim3(kBlock), 0, st,
@@ -559,7 +622,7 @@ int launch_reduce_scatter_accum(float* acc, const PtrTable& g, size_t count, int
     const size_t nvec = vec16 ? count / 8 : 0;
     unsigned blocks = 0;
     if (nvec) {
-        if (int e = grid_for(nvec, &blocks)) return e;
+        if (int e = grid_for(nvec, kRsaBlock, MICS_RSA_BPC, &blocks)) return e;
         switch (p) {
             case 1: rsa_launch_fixed<1>(acc, g, nvec, accumulate, blocks, st); break;
             case 2: rsa_launch_fixed<2>(acc, g, nvec, accumulate, blocks, st); break;
@@ -568,17 +631,17 @@ int launch_reduce_scatter_accum(float* acc, const PtrTable& g, size_t count, int
             case 16: rsa_launch_fixed<16>(acc, g, nvec, accumulate, blocks, st); break;
             default:
                 if (accumulate)
-                    hipLaunchKernelGGL((rsa_vec_anyp_kernel<true, kNT>), dim3(blocks), dim3(kBlock),
+                    hipLaunchKernelGGL(rsa_vec_anyp_kernel<true>, dim3(blocks), dim3(kRsaBlock),
                                        0, st, acc, g, p, nvec);
                 else
-                    hipLaunchKernelGGL((rsa_vec_anyp_kernel<false, kNT>), dim3(blocks), dim3(kBlock),
+                    hipLaunchKernelGGL(rsa_vec_anyp_kernel<false>, dim3(blocks), dim3(kRsaBlock),
                                        0, st, acc, g, p, nvec);
         }
         if (int e = launch_status()) return e;
     }
     const size_t first = nvec * 8;
     if (first < count) {
-        if (int e = grid_for(count - first, &blocks)) return e;
+        if (int e = grid_for(count - first, kBlock, kTailBpc, &blocks)) return e;
         if (accumulate)
             hipLaunchKernelGGL(rsa_scalar_kernel<true>, dim3(blocks), dim3(kBlock), 0, st, acc, g, p,
                                first, count);
@@ -597,21 +660,21 @@ int launch_replica_average(float* out, const PtrTable& a, size_t count, int r, f
     const size_t nvec = vec16 ? count / 4 : 0;
     unsigned blocks = 0;
     if (nvec) {
-        if (int e = grid_for((nvec + 1) / 2, &blocks)) return e;
+        if (int e = grid_for((nvec + 1) / 2, kAvgBlock, MICS_AVG_BPC, &blocks)) return e;
         switch (r) {
             case 1: avg_launch_fixed<1>(out, a, scale, nvec, blocks, st); break;
             case 2: avg_launch_fixed<2>(out, a, scale, nvec, blocks, st); break;
             case 4: avg_launch_fixed<4>(out, a, scale, nvec, blocks, st); break;
             case 8: avg_launch_fixed<8>(out, a, scale, nvec, blocks, st); break;
             default:
-                hipLaunchKernelGGL((avg_vec_anyr_kernel<kNT>), dim3(blocks), dim3(kBlock), 0, st, out,
+                hipLaunchKernelGGL(avg_vec_anyr_kernel, dim3(blocks), dim3(kAvgBlock), 0, st, out,
                                    a, r, scale, nvec);
         }
         if (int e = launch_status()) return e;
     }
     const size_t first = nvec * 4;
     if (first < count) {
-        if (int e = grid_for(count - first, &blocks)) return e;
+        if (int e = grid_for(count - first, kBlock, kTailBpc, &blocks)) return e;
         hipLaunchKernelGGL(avg_scalar_kernel, dim3(blocks), dim3(kBlock), 0, st, out, a, r, scale,
                            first, count);
         if (int e = launch_status()) return e;
@@ -623,21 +686,21 @@ int launch_adam(float* master, float* exp_avg, float* exp_avg_sq, uint16_t* para
                 const float* grad, size_t count, const AdamScalars& hp, bool vec16, void* stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    const size_t nvec = vec16 ? count / 8 : 0;
+    const size_t nvec = vec16 ? count / 4 : 0;
     unsigned blocks = 0;
     if (nvec) {
-        if (int e = grid_for(nvec, &blocks)) return e;
+        if (int e = grid_for((nvec + 1) / 2, kAdamBlock, MICS_ADAM_BPC, &blocks)) return e;
         if (param_bf16)
-            hipLaunchKernelGGL((adam_vec_kernel<true, kNT>), dim3(blocks), dim3(kBlock), 0, st, master,
+            hipLaunchKernelGGL(adam_vec_kernel<true>, dim3(blocks), dim3(kAdamBlock), 0, st, master,
                                exp_avg, exp_avg_sq, param_bf16, grad, nvec, hp);
         else
-            hipLaunchKernelGGL((adam_vec_kernel<false, kNT>), dim3(blocks), dim3(kBlock), 0, st,
+            hipLaunchKernelGGL(adam_vec_kernel<false>, dim3(blocks), dim3(kAdamBlock), 0, st,
                                master, exp_avg, exp_avg_sq, param_bf16, grad, nvec, hp);
         if (int e = launch_status()) return e;
     }
-    const size_t first = nvec * 8;
+    const size_t first = nvec * 4;
     if (first < count) {
-        if (int e = grid_for(count - first, &blocks)) return e;
+        if (int e = grid_for(count - first, kBlock, kTailBpc, &blocks)) return e;
         if (param_bf16)
             hipLaunchKernelGGL(adam_scalar_kernel<true>, dim3(blocks), dim3(kBlock), 0, st, master,
                                exp_avg, exp_avg_sq, param_bf16, grad, first, count, hp);

@@ -108,6 +108,6 @@ def test_adam_argument_errors():
 def test_launch_knob_range():
     mics.mics_set_blocks_per_cu(0)
     with pytest.raises(mics.MicsError):
-        mics.mics_set_blocks_per_cu(65)
+        mics.mics_set_blocks_per_cu(4097)
     with pytest.raises(mics.MicsError):
         mics.mics_set_blocks_per_cu(-1)
