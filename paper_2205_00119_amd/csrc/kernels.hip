@@ -2,9 +2,13 @@
 //
 // All four steps stream every byte once and do at most a few operations per
 // element, so they are bound by HBM bandwidth, not by the matrix or vector
-// units.  The kernels therefore aim at: 128-bit global loads and stores, many
-// independent loads in flight per lane before the first use, no re-reads, and
-// grids of a few workgroups per compute unit that stride over the data.
+// units.  The kernels therefore aim at: 128-bit global loads and stores that
+// cover contiguous memory per wavefront instruction, all of a lane's loads in
+// flight before the first use, no re-reads, and grids with one pass per lane:
+// workgroups are dispatched in index order, so the lanes in flight cover a
+// compact window of every buffer that advances through memory (measured on
+// MI355X: a lane that owns several vectors a grid stride apart, or a small
+// persistent grid, loses 5-30 % of the bandwidth, stores most of all).
 //
 // Arithmetic rules (they make the results reproducible bit for bit):
 //   - no fused multiply-add (-ffp-contract=off and the pragma below),
@@ -30,13 +34,13 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 // Launch shape and cache hints per kernel family; the defaults are the measured best on
 // MI355X for the h = 8192, p = 16 shard shapes.  *_BLOCK = workgroup size, *_BPC = cap on
-// workgroups per compute unit (a grid that covers the data with one pass per lane when the
-// cap is not reached; lanes stride over the rest), *_NTL / *_NTS = non-temporal loads / stores.
+// workgroups per compute unit (the grid covers the data with one pass per lane unless the
+// cap is reached; lanes stride over the rest), *_NTL / *_NTS = non-temporal loads / stores.
 #ifndef MICS_REORDER_BLOCK
 #define MICS_REORDER_BLOCK 256
 #endif
 #ifndef MICS_REORDER_BPC
-#define MICS_REORDER_BPC 16
+#define MICS_REORDER_BPC 4096
 #endif
 #ifndef MICS_REORDER_NTL
 #define MICS_REORDER_NTL 1
@@ -45,10 +49,10 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #define MICS_REORDER_NTS 1
 #endif
 #ifndef MICS_RSA_BLOCK
-#define MICS_RSA_BLOCK 1024
+#define MICS_RSA_BLOCK 512
 #endif
 #ifndef MICS_RSA_BPC
-#define MICS_RSA_BPC 32
+#define MICS_RSA_BPC 4096
 #endif
 #ifndef MICS_RSA_NTL
 #define MICS_RSA_NTL 1
@@ -57,10 +61,10 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #define MICS_RSA_NTS 0
 #endif
 #ifndef MICS_AVG_BLOCK
-#define MICS_AVG_BLOCK 1024
+#define MICS_AVG_BLOCK 512
 #endif
 #ifndef MICS_AVG_BPC
-#define MICS_AVG_BPC 32
+#define MICS_AVG_BPC 4096
 #endif
 #ifndef MICS_AVG_NTL
 #define MICS_AVG_NTL 1
@@ -69,10 +73,10 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #define MICS_AVG_NTS 0
 #endif
 #ifndef MICS_ADAM_BLOCK
-#define MICS_ADAM_BLOCK 1024
+#define MICS_ADAM_BLOCK 256
 #endif
 #ifndef MICS_ADAM_BPC
-#define MICS_ADAM_BPC 32
+#define MICS_ADAM_BPC 4096
 #endif
 #ifndef MICS_ADAM_NTL
 #define MICS_ADAM_NTL 1
@@ -152,15 +156,13 @@ __global__ __launch_bounds__(kReorderBlock) void reorder_vec_kernel(
     const u32x4* __restrict__ s = (const u32x4*)src.ptr[l] + j * shard_vecs;
     u32x4* __restrict__ d = dst + g * shard_vecs;
 
+    // One vector per lane and pass.  Workgroups are dispatched in blockIdx order, so the lanes
+    // in flight cover one compact, advancing window of the source and of the destination; a
+    // lane that strides far ahead (several loads a grid stride apart) measurably lowers the
+    // achieved bandwidth, for loads and even more for stores.
     const size_t stride = (size_t)gridDim.x * kReorderBlock;
-    size_t i = (size_t)blockIdx.x * kReorderBlock + threadIdx.x;
-    for (; i + 3 * stride < nfull; i += 4 * stride) {   // four loads in flight per lane
-        u32x4 a = ld<kReorderNtl>(s + i), b = ld<kReorderNtl>(s + i + stride);
-        u32x4 c = ld<kReorderNtl>(s + i + 2 * stride), e = ld<kReorderNtl>(s + i + 3 * stride);
-        st<kReorderNts>(d + i, a); st<kReorderNts>(d + i + stride, b);
-        st<kReorderNts>(d + i + 2 * stride, c); st<kReorderNts>(d + i + 3 * stride, e);
-    }
-    for (; i < nfull; i += stride) st<kReorderNts>(d + i, ld<kReorderNtl>(s + i));
+    for (size_t i = (size_t)blockIdx.x * kReorderBlock + threadIdx.x; i < nfull; i += stride)
+        st<kReorderNts>(d + i, ld<kReorderNtl>(s + i));
 
     // ragged end of the logical buffer: fewer than 16 valid bytes remain
     const size_t tail_halves = (valid - nfull * 16) / 2;
@@ -360,7 +362,7 @@ __global__ __launch_bounds__(kBlock) void rsa_scalar_kernel(
 // ---------------------------------------------------------------------------
 // Step 2b: reduction of the replication-group all-reduce at the accumulation
 // boundary and the scaling to a mean (Section 3.4).  One lane owns 4 elements
-// per copy.  `out` may be copies[0]: a lane reads its elements of every copy
+// per copy and pass.  `out` may be copies[0]: a lane reads its elements of every copy
 // before it writes them, and no other lane touches them.
 // ---------------------------------------------------------------------------
 
@@ -369,21 +371,7 @@ __global__ __launch_bounds__(kAvgBlock) void avg_vec_kernel(
     float* out, SmallTable<R> a, float scale, size_t nvec)
 {
     const size_t stride = (size_t)gridDim.x * kAvgBlock;
-    size_t i = (size_t)blockIdx.x * kAvgBlock + threadIdx.x;
-    for (; i + stride < nvec; i += 2 * stride) {    // two vectors per copy in flight
-        f32x4 v[R], u[R];
-        #pragma unroll
-        for (int c = 0; c < R; ++c) {
-            v[c] = ld<kAvgNtl>((const f32x4*)a.ptr[c] + i);
-            u[c] = ld<kAvgNtl>((const f32x4*)a.ptr[c] + i + stride);
-        }
-        f32x4 sv = v[0], su = u[0];
-        #pragma unroll
-        for (int c = 1; c < R; ++c) { sv = sv + v[c]; su = su + u[c]; }
-        st<kAvgNts>((f32x4*)out + i, sv * scale);
-        st<kAvgNts>((f32x4*)out + i + stride, su * scale);
-    }
-    for (; i < nvec; i += stride) {
+    for (size_t i = (size_t)blockIdx.x * kAvgBlock + threadIdx.x; i < nvec; i += stride) {
         f32x4 v[R];
         #pragma unroll
         for (int c = 0; c < R; ++c) v[c] = ld<kAvgNtl>((const f32x4*)a.ptr[c] + i);
@@ -453,47 +441,33 @@ __device__ __forceinline__ void adam_element(float& w, float& m, float& v, float
     v = v_new;
 }
 
-// One lane owns two groups of 4 consecutive elements, a grid stride apart, so that every
-// load and store instruction of a wavefront covers one contiguous kilobyte (stores that
-// leave gaps between lanes reach memory as partial lines and cost extra traffic).
-// Eight 128-bit loads are in flight before the first use.
+// One lane owns 4 consecutive elements per pass, so that every load and store instruction of
+// a wavefront covers one contiguous kilobyte (stores that leave gaps between lanes reach
+// memory as partial lines and cost extra traffic).  Four 128-bit loads are in flight before
+// the first use; the bf16 parameters leave as one 64-bit store.
 template <bool BF16>
 __global__ __launch_bounds__(kAdamBlock) void adam_vec_kernel(
     float* __restrict__ master, float* __restrict__ exp_avg, float* __restrict__ exp_avg_sq,
     uint16_t* __restrict__ param_bf16, const float* __restrict__ grad, size_t nvec, AdamScalars hp)
 {
     const size_t stride = (size_t)gridDim.x * kAdamBlock;
-    for (size_t i0 = (size_t)blockIdx.x * kAdamBlock + threadIdx.x; i0 < nvec; i0 += 2 * stride) {
-        const size_t i1 = i0 + stride;
-        const bool two = i1 < nvec;
-        f32x4 g[2], w[2], m[2], v[2];
-        g[0] = ld<kAdamNtl>((const f32x4*)grad + i0);
-        w[0] = ld<kAdamNtl>((const f32x4*)master + i0);
-        m[0] = ld<kAdamNtl>((const f32x4*)exp_avg + i0);
-        v[0] = ld<kAdamNtl>((const f32x4*)exp_avg_sq + i0);
-        if (two) {
-            g[1] = ld<kAdamNtl>((const f32x4*)grad + i1);
-            w[1] = ld<kAdamNtl>((const f32x4*)master + i1);
-            m[1] = ld<kAdamNtl>((const f32x4*)exp_avg + i1);
-            v[1] = ld<kAdamNtl>((const f32x4*)exp_avg_sq + i1);
-        }
+    for (size_t i = (size_t)blockIdx.x * kAdamBlock + threadIdx.x; i < nvec; i += stride) {
+        f32x4 g = ld<kAdamNtl>((const f32x4*)grad + i);
+        f32x4 w = ld<kAdamNtl>((const f32x4*)master + i);
+        f32x4 m = ld<kAdamNtl>((const f32x4*)exp_avg + i);
+        f32x4 v = ld<kAdamNtl>((const f32x4*)exp_avg_sq + i);
         #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            if (h == 1 && !two) break;
-            #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float we = w[h][e], me = m[h][e], ve = v[h][e];
-                adam_element(we, me, ve, g[h][e], hp);
-                w[h][e] = we; m[h][e] = me; v[h][e] = ve;
-            }
-            const size_t i = h ? i1 : i0;
-            st<kAdamNts>((f32x4*)master + i, w[h]);
-            st<kAdamNts>((f32x4*)exp_avg + i, m[h]);
-            st<kAdamNts>((f32x4*)exp_avg_sq + i, v[h]);
-            if (BF16) {
-                u32x2 b = {bf16_pack(w[h].x, w[h].y), bf16_pack(w[h].z, w[h].w)};
-                st<kAdamNts>((u32x2*)param_bf16 + i, b);
-            }
+        for (int e = 0; e < 4; ++e) {
+            float we = w[e], me = m[e], ve = v[e];
+            adam_element(we, me, ve, g[e], hp);
+            w[e] = we; m[e] = me; v[e] = ve;
+        }
+        st<kAdamNts>((f32x4*)master + i, w);
+        st<kAdamNts>((f32x4*)exp_avg + i, m);
+        st<kAdamNts>((f32x4*)exp_avg_sq + i, v);
+        if (BF16) {
+            u32x2 b = {bf16_pack(w.x, w.y), bf16_pack(w.z, w.w)};
+            st<kAdamNts>((u32x2*)param_bf16 + i, b);
         }
     }
 }
@@ -599,8 +573,8 @@ int launch_reorder(void* dst, const PtrTable& src, size_t n_valid_bytes, size_t 
     hipStream_t st = (hipStream_t)stream;
     unsigned total = 0;
     if (vec16) {
-        // four vectors per lane and pass; spread the block budget over the p chunks
-        if (int e = grid_for(shard_bytes / 16 / 4 * (size_t)p + 1, kReorderBlock, MICS_REORDER_BPC, &total)) return e;
+        // spread the block budget over the p chunks
+        if (int e = grid_for(shard_bytes / 16 * (size_t)p, kReorderBlock, MICS_REORDER_BPC, &total)) return e;
         unsigned bx = (total + (unsigned)p - 1) / (unsigned)p;
         hipLaunchKernelGGL(reorder_vec_kernel, dim3(bx, (unsigned)p), dim3(kReorderBlock), 0, st,
                            (u32x4*)dst, src, shard_bytes / 16, n_valid_bytes, k);
@@ -660,7 +634,7 @@ int launch_replica_average(float* out, const PtrTable& a, size_t count, int r, f
     const size_t nvec = vec16 ? count / 4 : 0;
     unsigned blocks = 0;
     if (nvec) {
-        if (int e = grid_for((nvec + 1) / 2, kAvgBlock, MICS_AVG_BPC, &blocks)) return e;
+        if (int e = grid_for(nvec, kAvgBlock, MICS_AVG_BPC, &blocks)) return e;
         switch (r) {
             case 1: avg_launch_fixed<1>(out, a, scale, nvec, blocks, st); break;
             case 2: avg_launch_fixed<2>(out, a, scale, nvec, blocks, st); break;
@@ -689,7 +663,7 @@ int launch_adam(float* master, float* exp_avg, float* exp_avg_sq, uint16_t* para
     const size_t nvec = vec16 ? count / 4 : 0;
     unsigned blocks = 0;
     if (nvec) {
-        if (int e = grid_for((nvec + 1) / 2, kAdamBlock, MICS_ADAM_BPC, &blocks)) return e;
+        if (int e = grid_for(nvec, kAdamBlock, MICS_ADAM_BPC, &blocks)) return e;
         if (param_bf16)
             hipLaunchKernelGGL(adam_vec_kernel<true>, dim3(blocks), dim3(kAdamBlock), 0, st, master,
                                exp_avg, exp_avg_sq, param_bf16, grad, nvec, hp);
