@@ -160,7 +160,29 @@ def hier_gather_reorder(T: Sequence[np.ndarray], n_valid: int, S: int, p: int) -
     return out
 
 
+def hier_gather_reorder_coalesced(T: Sequence[np.ndarray], segs, p: int, out: np.ndarray) -> np.ndarray:
+    """Many tensors gathered at once (the paper's coalesced all-gather, Section 4): the per-tensor
+    reorder applied to each tensor in turn.  ``segs`` = (numel, shard_elems, src_offset,
+    dst_offset) per tensor; tensor t occupies (p/k)*shard_elems elements from src_offset in every
+    stage-1 buffer and numel elements from dst_offset in ``out`` (written in place)."""
+    k = len(T)
+    for numel, S, src_off, dst_off in segs:
+        sub = [np.ascontiguousarray(t[src_off:src_off + (p // k) * S]) for t in T]
+        out[dst_off:dst_off + numel] = hier_gather_reorder(sub, numel, S, p)
+    return out
+
+
 # ---- 2-hop gradient synchronisation (Section 3.4) -------------------------------
+
+def reduce_scatter_accum_coalesced(acc, grads: Sequence[np.ndarray], segs, accumulate: bool) -> np.ndarray:
+    """Many tensors reduced at once (coalesced reduce-scatter, Section 4): for every segment
+    (count, _, src_offset, dst_offset) the plain reduce-scatter-accumulate of elements
+    [src_offset, src_offset+count) of the rank buffers into acc[dst_offset:dst_offset+count]."""
+    acc = _c(acc, np.float32)
+    for count, _, src_off, dst_off in segs:
+        reduce_scatter_accum(acc[dst_off:dst_off + count], grads, src_off, accumulate)
+    return acc
+
 
 def reduce_scatter_accum(acc, grads: Sequence[np.ndarray], elem_offset: int, accumulate: bool,
                          f64: bool = False) -> np.ndarray:

@@ -92,6 +92,54 @@ CONFIGS = {
 }
 
 
+# ---- one layer as its tensors (coalesced collectives, Section 4) -------------------------
+
+def layer_tensors(h: int):
+    """(name, elements) of the 16 tensors of one transformer layer (Table 1: intermediate = 4h)."""
+    t = []
+    for name in ("attn.q", "attn.k", "attn.v", "attn.out"):
+        t += [(name + ".weight", h * h), (name + ".bias", h)]
+    t += [("ln1.weight", h), ("ln1.bias", h)]
+    t += [("ffn.up.weight", 4 * h * h), ("ffn.up.bias", 4 * h)]
+    t += [("ffn.down.weight", 4 * h * h), ("ffn.down.bias", h)]
+    t += [("ln2.weight", h), ("ln2.bias", h)]
+    assert sum(n for _, n in t) == layer_elems(h)
+    return t
+
+
+@dataclass(frozen=True)
+class CoalescedLayout:
+    """Where each separately sharded tensor lives in the four kinds of buffer.  All offsets
+    are in elements.  S[t] = shard size of tensor t."""
+    numel: tuple      # logical elements per tensor
+    S: tuple          # shard elements per tensor
+    stage1_off: tuple  # in every stage-1 buffer: (p/k)*S[t] elements from here
+    flat_off: tuple    # in the gathered flat parameter: numel[t] elements from here
+    grad_off: tuple    # in every rank's gradient buffer: p*S[t] elements from here
+    shard_off: tuple   # in a rank's shard buffers (acc, master, ...): S[t] elements from here
+
+    @property
+    def stage1_len(self):
+        return self.stage1_off[-1] if self.stage1_off else 0
+
+    def reorder_segments(self):
+        return [(self.numel[t], self.S[t], self.stage1_off[t], self.flat_off[t]) for t in range(len(self.S))]
+
+    def reduce_segments(self, g: int):
+        return [(self.S[t], 0, self.grad_off[t] + g * self.S[t], self.shard_off[t]) for t in range(len(self.S))]
+
+
+def coalesced_layout(numels, p: int, k: int, align: int = 8, flat_align: int = 1) -> CoalescedLayout:
+    S = [shard_elems(n, p, align) for n in numels]
+    stage1, flat, grad, shard = [0], [0], [0], [0]
+    for n, s in zip(numels, S):
+        stage1.append(stage1[-1] + (p // k) * s)
+        flat.append(-(-(flat[-1] + n) // flat_align) * flat_align)
+        grad.append(grad[-1] + p * s)
+        shard.append(shard[-1] + s)
+    return CoalescedLayout(tuple(numels), tuple(S), tuple(stage1), tuple(flat), tuple(grad), tuple(shard))
+
+
 # ---- tables --------------------------------------------------------------------------
 
 def _f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
