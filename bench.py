@@ -40,6 +40,10 @@ def parse_args():
     ap.add_argument("--config", default="h8192")
     ap.add_argument("--view", choices=["rank", "group"], default="rank")
     ap.add_argument("--rank", type=int, default=5, help="which group rank's shard is simulated")
+    ap.add_argument("--coalesced", action="store_true",
+                    help="treat the layer as its 16 separately sharded tensors (coalesced gather / "
+                         "reduce-scatter): a1 and a2 run through the *_coalesced entry points on "
+                         "full-length rank gradient buffers (4 sets, cycled over the micro-steps)")
     ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -93,24 +97,49 @@ def main():
         synth.fill_device(t.data_ptr(), key, x0, t.numel(), table.data_ptr(), elem_bytes,
                           outl.data_ptr() if outl is not None else 0, frac, sh)
 
-    # a1: the gathered-but-unordered parameter W = [T_0 .. T_{k-1}], T_l = [C_l, C_{k+l}, ...]
-    W = torch.empty(n_pad, dtype=torch.int16, device=dev)
     nodes = p // k
-    for g in range(p):
-        j, l = divmod(g, k)
-        slot = (l * nodes + j) * S
-        fill(W[slot:slot + S], synth.stream_key(cfg.seed, synth.ROLE_PARAM, 0, 0, g), 0, tab_p, 2)
-    T_views = [W[l * nodes * S:(l + 1) * nodes * S] for l in range(k)]
     F = torch.empty(N, dtype=torch.int16, device=dev)
+    if not args.coalesced:
+        # a1: the gathered-but-unordered parameter W = [T_0 .. T_{k-1}], T_l = [C_l, C_{k+l}, ...]
+        W = torch.empty(n_pad, dtype=torch.int16, device=dev)
+        for g in range(p):
+            j, l = divmod(g, k)
+            slot = (l * nodes + j) * S
+            fill(W[slot:slot + S], synth.stream_key(cfg.seed, synth.ROLE_PARAM, 0, 0, g), 0, tab_p, 2)
+        T_views = [W[l * nodes * S:(l + 1) * nodes * S] for l in range(k)]
 
-    # a2: per micro-step, p gradient buffers covering the elements this call owns
-    n_sets = 1 if group else s
-    grads = torch.empty((n_sets, p, count), dtype=torch.int16, device=dev)
-    for t in range(n_sets):
-        for q in range(p):
-            fill(grads[t, q], synth.stream_key(cfg.seed, synth.ROLE_GRAD, 0, t, q), offset, tab_g, 2,
-                 tab_go, cfg.outlier_frac)
-    grad_tables = [[grads[t % n_sets, q] for q in range(p)] for t in range(s)]
+        # a2: per micro-step, p gradient buffers covering the elements this call owns
+        n_sets = 1 if group else s
+        grads = torch.empty((n_sets, p, count), dtype=torch.int16, device=dev)
+        for t in range(n_sets):
+            for q in range(p):
+                fill(grads[t, q], synth.stream_key(cfg.seed, synth.ROLE_GRAD, 0, t, q), offset, tab_g, 2,
+                     tab_go, cfg.outlier_frac)
+        grad_tables = [[grads[t % n_sets, q] for q in range(p)] for t in range(s)]
+    else:
+        if group or cfg.name == "tiny" or cfg.align != 8:
+            print("--coalesced needs a transformer-layer configuration in rank view", file=sys.stderr)
+            sys.exit(2)
+        h = int(cfg.name[1:])
+        lay = synth.coalesced_layout([n for _, n in synth.layer_tensors(h)], p, k, align=8)
+        assert lay.shard_off[-1] == S and lay.flat_off[-1] == N
+        # a1: k separate stage-1 buffers, tensor after tensor, each holding that tensor's p/k chunks
+        T_views = [torch.empty(lay.stage1_off[-1], dtype=torch.int16, device=dev) for _ in range(k)]
+        for t, St in enumerate(lay.S):
+            for g in range(p):
+                j, l = divmod(g, k)
+                at = lay.stage1_off[t] + j * St
+                fill(T_views[l][at:at + St], synth.stream_key(cfg.seed, synth.ROLE_PARAM, t, 0, g), 0, tab_p, 2)
+        reorder_segs = mics._segments(lay.reorder_segments())
+        # a2: every rank's full gradient buffer (all tensors, p*S_t each); the rank reads its slices
+        n_sets = min(s, 4)
+        grads = torch.empty((n_sets, p, lay.grad_off[-1]), dtype=torch.int16, device=dev)
+        for t in range(n_sets):
+            for q in range(p):
+                fill(grads[t, q], synth.stream_key(cfg.seed, synth.ROLE_GRAD, 0, t, q), 0, tab_g, 2,
+                     tab_go, cfg.outlier_frac)
+        grad_tables = [[grads[t % n_sets, q] for q in range(p)] for t in range(s)]
+        reduce_segs = mics._segments(lay.reduce_segments(args.rank))
 
     # a3: this replica's accumulator plus the r-1 copies that arrive from the other replicas
     acc = torch.empty(count, dtype=torch.float32, device=dev)
@@ -137,11 +166,17 @@ def main():
         marks = [torch.cuda.Event(enable_timing=True) for _ in range(5)] if timed else None
         if timed:
             marks[0].record(stream)
-        mics.mics_hier_gather_reorder(F, T_views, N, S, p, k, 2, stream=sh)
+        if args.coalesced:
+            mics.mics_hier_gather_reorder_coalesced(F, T_views, reorder_segs, p, k, 2, stream=sh)
+        else:
+            mics.mics_hier_gather_reorder(F, T_views, N, S, p, k, 2, stream=sh)
         if timed:
             marks[1].record(stream)
         for t in range(s):
-            mics.mics_reduce_scatter_accum(acc, grad_tables[t], 0, count, t > 0, stream=sh)
+            if args.coalesced:
+                mics.mics_reduce_scatter_accum_coalesced(acc, grad_tables[t], reduce_segs, t > 0, stream=sh)
+            else:
+                mics.mics_reduce_scatter_accum(acc, grad_tables[t], 0, count, t > 0, stream=sh)
         if timed:
             marks[2].record(stream)
         mics.mics_replica_average(avg, copies, count, scale, stream=sh)
@@ -153,6 +188,9 @@ def main():
             all_marks.append(marks)
 
     if args.calibration_copy:
+        if args.coalesced:
+            print("--calibration-copy is for the flat layout", file=sys.stderr)
+            sys.exit(2)
         mics.mics_hier_gather_reorder(F, [W], N, N, 1, 1, 2, stream=sh)
         torch.cuda.synchronize()
     for it in range(1, args.warmup + 1):
@@ -199,8 +237,9 @@ def main():
         "config": {
             "workload": f"{cfg.name}: one transformer layer h={cfg.name[1:]} N={N}, p={p} "
                         f"({nodes} nodes x k={k}), r={r}, s={s}, {args.view} view "
-                        f"({count} elements per reduce/average/Adam call)",
-            "view": args.view, "N": N, "S": S, "p": p, "k": k, "r": r, "s": s,
+                        f"({count} elements per reduce/average/Adam call)"
+                        + (", coalesced: 16 separately sharded tensors" if args.coalesced else ""),
+            "view": args.view, "coalesced": bool(args.coalesced), "N": N, "S": S, "p": p, "k": k, "r": r, "s": s,
             "algorithmic_bytes_per_step": b_step,
         },
         "kernels": {
@@ -209,7 +248,8 @@ def main():
             for name, b in (("a1", b_a1), ("a2", b_a2), ("a3", b_a3), ("a4", b_a4))
         },
         "roofline": {
-            "kernel": f"rsa_vec_kernel<{p}> (mics_reduce_scatter_accum)",
+            "kernel": (f"rsa_seg_kernel<{p}> (mics_reduce_scatter_accum_coalesced)" if args.coalesced
+                       else f"rsa_vec_kernel<{p}> (mics_reduce_scatter_accum)"),
             "bound": "hbm",
             "achieved": round(a2_gbps, 1),
             "peak": PEAK_HBM_GBPS,
@@ -217,7 +257,7 @@ def main():
             "frac": round(a2_gbps / PEAK_HBM_GBPS, 4),
             "avg_launch_ms": round(a2_launch_ms, 5),
             "algorithmic_bytes_per_launch": b_a2 // s,
-            "traffic": MEASURED_TRAFFIC.get((cfg.name, args.view)),
+            "traffic": None if args.coalesced else MEASURED_TRAFFIC.get((cfg.name, args.view)),
         },
     }
     if not args.no_cpu_baseline:

@@ -160,6 +160,44 @@ int mics_adam_shard(float* master, float* exp_avg, float* exp_avg_sq,
                     float weight_decay, int step, void* stream);
 
 /*
+ * One separately sharded tensor of a coalesced call.  The paper's coalesced collectives
+ * (Section 4, "Coalesced communication APIs": all_gather_coalesced, reduce_scatter_coalesced)
+ * launch the per-tensor operations of many tensors at once, with no staging copy; the two
+ * entry points below are their on-device halves.  Offsets are in elements.
+ */
+typedef struct mics_segment {
+    size_t numel;        /* reorder: logical elements of the tensor; reduce: elements to reduce */
+    size_t shard_elems;  /* reorder: S of this tensor (numel <= p*S); reduce: ignored          */
+    size_t src_offset;   /* where the tensor's region starts inside every source buffer        */
+    size_t dst_offset;   /* where the tensor's region starts inside the destination            */
+} mics_segment;
+
+/*
+ * mics_hier_gather_reorder for n_segs tensors at once: for every segment t and every flat
+ * index x < numel_t, with g = x div S_t, i = x mod S_t, j = g div k, l = g mod k,
+ *     dst_flat[dst_offset_t + x] = stage1_bufs[l][src_offset_t + j*S_t + i].
+ * Tensor t occupies (p/k)*S_t elements from src_offset_t in every stage-1 buffer and numel_t
+ * elements from dst_offset_t in dst_flat; regions of different tensors must not overlap.
+ * segs is a HOST array.  Tensors whose addresses and shard sizes are multiples of 16 bytes
+ * share one launch (per 48 tensors); any other tensor is moved by a launch of its own.
+ */
+int mics_hier_gather_reorder_coalesced(void* dst_flat, const void* const* stage1_bufs,
+                                       const mics_segment* segs, int n_segs, int p, int k,
+                                       int elem_bytes, void* stream);
+
+/*
+ * mics_reduce_scatter_accum for n_segs tensors at once: for every segment t and i < numel_t
+ *     acc[dst_offset_t + i] = (accumulate ? acc[dst_offset_t + i] : +0)
+ *                             + (((g_0[src_offset_t + i] + g_1[...]) + ...) + g_{p-1}[...]),
+ * same arithmetic and order as mics_reduce_scatter_accum.  For rank g of a partition group
+ * whose gradient buffers hold tensor t at offset o_t (p*S_t elements) and whose shard buffer
+ * holds it at offset a_t: numel = S_t, src_offset = o_t + g*S_t, dst_offset = a_t.
+ */
+int mics_reduce_scatter_accum_coalesced(float* acc, const uint16_t* const* grads_bf16,
+                                        const mics_segment* segs, int n_segs, int p,
+                                        int accumulate, void* stream);
+
+/*
  * Launch-shape knob for measurements (not part of the method): sets how many
  * workgroups per compute unit the streaming kernels of later calls launch at
  * most; 0 restores the built-in choice.  Process-wide.  Returns MICS_OK or

@@ -24,7 +24,7 @@ MICS_MAX_GROUP = 128
 EXPORTS = (
     "mics_version", "mics_last_error", "mics_shard_elems", "mics_set_blocks_per_cu",
     "mics_hier_gather_reorder", "mics_reduce_scatter_accum", "mics_replica_average",
-    "mics_adam_shard",
+    "mics_adam_shard", "mics_hier_gather_reorder_coalesced", "mics_reduce_scatter_accum_coalesced",
 )
 
 
@@ -63,6 +63,25 @@ lib.mics_replica_average.argtypes = [_vp, _vp, _sz, _i, _f, _vp]
 lib.mics_replica_average.restype = _i
 lib.mics_adam_shard.argtypes = [_vp, _vp, _vp, _vp, _vp, _sz, _f, _f, _f, _f, _f, _i, _vp]
 lib.mics_adam_shard.restype = _i
+
+
+class mics_segment(ctypes.Structure):
+    """One separately sharded tensor of a coalesced call (offsets and sizes in elements)."""
+    _fields_ = [("numel", ctypes.c_size_t), ("shard_elems", ctypes.c_size_t),
+                ("src_offset", ctypes.c_size_t), ("dst_offset", ctypes.c_size_t)]
+
+
+lib.mics_hier_gather_reorder_coalesced.argtypes = [_vp, _vp, ctypes.POINTER(mics_segment), _i, _i, _i,
+                                                   _i, _vp]
+lib.mics_hier_gather_reorder_coalesced.restype = _i
+lib.mics_reduce_scatter_accum_coalesced.argtypes = [_vp, _vp, ctypes.POINTER(mics_segment), _i, _i, _i,
+                                                    _vp]
+lib.mics_reduce_scatter_accum_coalesced.restype = _i
+
+
+def _segments(segs) -> ctypes.Array:
+    """(numel, shard_elems, src_offset, dst_offset) tuples -> C array of mics_segment."""
+    return (mics_segment * len(segs))(*[mics_segment(*map(int, sg)) for sg in segs])
 
 
 def _check(rc: int) -> None:
@@ -139,3 +158,24 @@ def mics_adam_shard(master, exp_avg, exp_avg_sq, param_bf16, grad, count: int, *
     _check(lib.mics_adam_shard(_dev_ptr(master), _dev_ptr(exp_avg), _dev_ptr(exp_avg_sq),
                                _dev_ptr(param_bf16), _dev_ptr(grad), count, lr, beta1, beta2, eps,
                                weight_decay, step, _stream(stream)))
+
+
+def mics_hier_gather_reorder_coalesced(dst_flat, stage1_bufs: Sequence, segs, p: int, k: int,
+                                       elem_bytes: int, stream=None) -> None:
+    """The gather reorder for many separately sharded tensors in one call; ``segs`` holds
+    (numel, shard_elems, src_offset, dst_offset) per tensor."""
+    if len(stage1_bufs) != k:
+        raise ValueError(f"expected k = {k} stage-1 buffers, got {len(stage1_bufs)}")
+    arr = segs if isinstance(segs, ctypes.Array) else _segments(segs)
+    _check(lib.mics_hier_gather_reorder_coalesced(_dev_ptr(dst_flat), _table(stage1_bufs), arr, len(arr),
+                                                  p, k, elem_bytes, _stream(stream)))
+
+
+def mics_reduce_scatter_accum_coalesced(acc, grads_bf16: Sequence, segs, accumulate: bool,
+                                        stream=None) -> None:
+    """Reduce-scatter-accumulate for many tensors in one call; ``segs`` holds
+    (count, 0, src_offset, dst_offset) per tensor."""
+    arr = segs if isinstance(segs, ctypes.Array) else _segments(segs)
+    _check(lib.mics_reduce_scatter_accum_coalesced(_dev_ptr(acc), _table(grads_bf16), arr, len(arr),
+                                                   len(grads_bf16), int(bool(accumulate)),
+                                                   _stream(stream)))

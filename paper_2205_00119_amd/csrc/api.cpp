@@ -210,4 +210,156 @@ int mics_adam_shard(float* master, float* exp_avg, float* exp_avg_sq,
     return err ? hip_fail(fn, err) : MICS_OK;
 }
 
+int mics_hier_gather_reorder_coalesced(void* dst_flat, const void* const* stage1_bufs,
+                                       const mics_segment* segs, int n_segs, int p, int k,
+                                       int elem_bytes, void* stream)
+{
+    const char* fn = "mics_hier_gather_reorder_coalesced";
+    if (elem_bytes != 2 && elem_bytes != 4)
+        return fail(MICS_ERR_UNSUPPORTED, "%s: elem_bytes = %d, must be 2 or 4", fn, elem_bytes);
+    if (p < 1 || p > MICS_MAX_GROUP)
+        return fail(MICS_ERR_INVALID_ARG, "%s: p = %d not in [1, %d]", fn, p, MICS_MAX_GROUP);
+    if (k < 1 || k > p)
+        return fail(MICS_ERR_INVALID_ARG, "%s: k = %d not in [1, p = %d]", fn, k, p);
+    if (p % k != 0)
+        return fail(MICS_ERR_INVALID_ARG, "%s: p = %d is not divisible by k = %d", fn, p, k);
+    if (n_segs < 0) return fail(MICS_ERR_INVALID_ARG, "%s: n_segs = %d is negative", fn, n_segs);
+    if (n_segs == 0) return MICS_OK;
+    if (!segs) return fail(MICS_ERR_INVALID_ARG, "%s: segs is NULL", fn);
+    if (!stage1_bufs) return fail(MICS_ERR_INVALID_ARG, "%s: stage1_bufs is NULL", fn);
+    if (!dst_flat) return fail(MICS_ERR_INVALID_ARG, "%s: dst_flat is NULL", fn);
+    const size_t eb = (size_t)elem_bytes;
+    if (!aligned(dst_flat, eb))
+        return fail(MICS_ERR_ALIGNMENT, "%s: dst_flat not aligned to %d bytes", fn, elem_bytes);
+    const size_t limit = SIZE_MAX / 8 / (size_t)p;   // keeps every byte offset below SIZE_MAX / 2
+    size_t dst_lo = SIZE_MAX, dst_hi = 0, src_lo = SIZE_MAX, src_hi = 0, total = 0;
+    for (int t = 0; t < n_segs; ++t) {
+        const mics_segment& sg = segs[t];
+        if (sg.shard_elems > limit || sg.src_offset > limit || sg.dst_offset > limit)
+            return fail(MICS_ERR_INVALID_ARG, "%s: segment %d: sizes or offsets overflow", fn, t);
+        if (sg.numel > (size_t)p * sg.shard_elems)
+            return fail(MICS_ERR_INVALID_ARG, "%s: segment %d: numel = %zu exceeds p * shard_elems = %zu",
+                        fn, t, sg.numel, (size_t)p * sg.shard_elems);
+        if (sg.numel == 0) continue;
+        total += sg.numel;
+        if (sg.dst_offset < dst_lo) dst_lo = sg.dst_offset;
+        if (sg.dst_offset + sg.numel > dst_hi) dst_hi = sg.dst_offset + sg.numel;
+        if (sg.src_offset < src_lo) src_lo = sg.src_offset;
+        const size_t src_end = sg.src_offset + (size_t)(p / k) * sg.shard_elems;
+        if (src_end > src_hi) src_hi = src_end;
+    }
+    mics::PtrTable tab{};
+    bool bases16 = aligned(dst_flat, 16);
+    for (int l = 0; l < k; ++l) {
+        const void* s = stage1_bufs[l];
+        if (!s) return fail(MICS_ERR_INVALID_ARG, "%s: stage1_bufs[%d] is NULL", fn, l);
+        if (!aligned(s, eb))
+            return fail(MICS_ERR_ALIGNMENT, "%s: stage1_bufs[%d] not aligned to %d bytes", fn, l,
+                        elem_bytes);
+        if (total && overlaps((const char*)dst_flat + dst_lo * eb, (dst_hi - dst_lo) * eb,
+                              (const char*)s + src_lo * eb, (src_hi - src_lo) * eb))
+            return fail(MICS_ERR_INVALID_ARG, "%s: dst_flat overlaps stage1_bufs[%d]", fn, l);
+        bases16 = bases16 && aligned(s, 16);
+        tab.ptr[l] = s;
+    }
+    if (total == 0) return MICS_OK;
+
+    // 16-byte clean tensors are batched; the rest go through the single-tensor path one by one
+    mics::Segment batch[mics::kMaxSegPerLaunch];
+    int nb = 0;
+    for (int t = 0; t <= n_segs; ++t) {
+        const bool last = (t == n_segs);
+        bool batched = false;
+        if (!last && segs[t].numel) {
+            const mics_segment& sg = segs[t];
+            batched = bases16 && (sg.shard_elems * eb) % 16 == 0 && (sg.src_offset * eb) % 16 == 0 &&
+                      (sg.dst_offset * eb) % 16 == 0;
+            if (batched) {
+                batch[nb].numel = sg.numel; batch[nb].shard_elems = sg.shard_elems;
+                batch[nb].src_offset = sg.src_offset; batch[nb].dst_offset = sg.dst_offset;
+                ++nb;
+            } else {
+                mics::PtrTable one{};
+                for (int l = 0; l < k; ++l) one.ptr[l] = (const char*)tab.ptr[l] + sg.src_offset * eb;
+                int err = mics::launch_reorder((char*)dst_flat + sg.dst_offset * eb, one, sg.numel * eb,
+                                               sg.shard_elems * eb, p, k, false, stream);
+                if (err) return hip_fail(fn, err);
+            }
+        }
+        if (nb == mics::kMaxSegPerLaunch || (last && nb)) {
+            int err = mics::launch_reorder_coalesced(dst_flat, tab, batch, nb, p, k, elem_bytes, stream);
+            if (err) return hip_fail(fn, err);
+            nb = 0;
+        }
+    }
+    return MICS_OK;
+}
+
+int mics_reduce_scatter_accum_coalesced(float* acc, const uint16_t* const* grads_bf16,
+                                        const mics_segment* segs, int n_segs, int p,
+                                        int accumulate, void* stream)
+{
+    const char* fn = "mics_reduce_scatter_accum_coalesced";
+    if (p < 1 || p > MICS_MAX_GROUP)
+        return fail(MICS_ERR_INVALID_ARG, "%s: p = %d not in [1, %d]", fn, p, MICS_MAX_GROUP);
+    if (n_segs < 0) return fail(MICS_ERR_INVALID_ARG, "%s: n_segs = %d is negative", fn, n_segs);
+    if (n_segs == 0) return MICS_OK;
+    if (!segs) return fail(MICS_ERR_INVALID_ARG, "%s: segs is NULL", fn);
+    if (!grads_bf16) return fail(MICS_ERR_INVALID_ARG, "%s: grads_bf16 is NULL", fn);
+    if (!acc) return fail(MICS_ERR_INVALID_ARG, "%s: acc is NULL", fn);
+    if (!aligned(acc, 4)) return fail(MICS_ERR_ALIGNMENT, "%s: acc not aligned to 4 bytes", fn);
+    const size_t limit = SIZE_MAX / 16;
+    size_t dst_lo = SIZE_MAX, dst_hi = 0, src_lo = SIZE_MAX, src_hi = 0, total = 0;
+    for (int t = 0; t < n_segs; ++t) {
+        const mics_segment& sg = segs[t];
+        if (sg.numel > limit || sg.src_offset > limit || sg.dst_offset > limit)
+            return fail(MICS_ERR_INVALID_ARG, "%s: segment %d: sizes or offsets overflow", fn, t);
+        if (sg.numel == 0) continue;
+        total += sg.numel;
+        if (sg.dst_offset < dst_lo) dst_lo = sg.dst_offset;
+        if (sg.dst_offset + sg.numel > dst_hi) dst_hi = sg.dst_offset + sg.numel;
+        if (sg.src_offset < src_lo) src_lo = sg.src_offset;
+        if (sg.src_offset + sg.numel > src_hi) src_hi = sg.src_offset + sg.numel;
+    }
+    mics::PtrTable tab{};
+    bool bases16 = aligned(acc, 16);
+    for (int q = 0; q < p; ++q) {
+        const uint16_t* g = grads_bf16[q];
+        if (!g) return fail(MICS_ERR_INVALID_ARG, "%s: grads_bf16[%d] is NULL", fn, q);
+        if (!aligned(g, 2))
+            return fail(MICS_ERR_ALIGNMENT, "%s: grads_bf16[%d] not aligned to 2 bytes", fn, q);
+        if (total && overlaps(acc + dst_lo, (dst_hi - dst_lo) * 4, g + src_lo, (src_hi - src_lo) * 2))
+            return fail(MICS_ERR_INVALID_ARG, "%s: acc overlaps grads_bf16[%d]", fn, q);
+        bases16 = bases16 && aligned(g, 16);
+        tab.ptr[q] = g;
+    }
+    if (total == 0) return MICS_OK;
+
+    mics::Segment batch[mics::kMaxSegPerLaunch];
+    int nb = 0;
+    for (int t = 0; t <= n_segs; ++t) {
+        const bool last = (t == n_segs);
+        if (!last && segs[t].numel) {
+            const mics_segment& sg = segs[t];
+            if (bases16 && sg.src_offset % 8 == 0 && sg.dst_offset % 4 == 0) {
+                batch[nb].numel = sg.numel; batch[nb].shard_elems = 0;
+                batch[nb].src_offset = sg.src_offset; batch[nb].dst_offset = sg.dst_offset;
+                ++nb;
+            } else {
+                mics::PtrTable one{};
+                for (int q = 0; q < p; ++q) one.ptr[q] = (const uint16_t*)tab.ptr[q] + sg.src_offset;
+                int err = mics::launch_reduce_scatter_accum(acc + sg.dst_offset, one, sg.numel, p,
+                                                            accumulate != 0, false, stream);
+                if (err) return hip_fail(fn, err);
+            }
+        }
+        if (nb == mics::kMaxSegPerLaunch || (last && nb)) {
+            int err = mics::launch_reduce_coalesced(acc, tab, batch, nb, p, accumulate != 0, stream);
+            if (err) return hip_fail(fn, err);
+            nb = 0;
+        }
+    }
+    return MICS_OK;
+}
+
 }  // extern "C"

@@ -40,6 +40,21 @@ int launch_adam(float* master, float* exp_avg, float* exp_avg_sq,
                 uint16_t* param_bf16, const float* grad, size_t count,
                 const AdamScalars& hp, bool vec16, void* stream);
 
+// Segment records travel in the kernel-argument segment: at most this many per launch.
+constexpr int kMaxSegPerLaunch = 48;
+
+// One separately sharded tensor of a coalesced call (mirrors mics_segment; elements).
+struct Segment {
+    size_t numel, shard_elems, src_offset, dst_offset;
+};
+
+// Every segment satisfies the 16-byte conditions of the vector kernels (the caller routes the
+// others through the single-tensor launchers).  For the reduction, numel = elements to reduce.
+int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs, int n, int p,
+                             int k, int elem_bytes, void* stream);
+int launch_reduce_coalesced(float* acc, const PtrTable& grads, const Segment* segs, int n, int p,
+                            bool accumulate, void* stream);
+
 // 0 = built-in choice.
 void set_blocks_per_cu(int n);
 

@@ -23,7 +23,7 @@ def declared_functions():
 
 def test_library_exports_every_declared_function():
     names = declared_functions()
-    assert len(names) >= 8
+    assert len(names) >= 10
     for name in names:
         assert hasattr(mics.lib, name), f"{name} declared in mics.h but not exported"
     assert sorted(set(names)) == sorted(mics.EXPORTS)
@@ -103,6 +103,26 @@ def test_adam_argument_errors():
     expect(mics.MICS_ERR_INVALID_ARG, "param_bf16 overlaps grad", f, w, m, v, g + 8, g, 8, step=1, stream=0, **hp)
     expect(mics.MICS_ERR_INVALID_ARG, "beta1", f, w, m, v, pb, g, 8, step=1, stream=0, **dict(hp, beta1=1.0))
     f(w, m, v, pb, g, 0, step=1, stream=0, **hp)
+
+
+def test_coalesced_argument_errors():
+    f = mics.mics_hier_gather_reorder_coalesced
+    T = [A + BUF * (i + 1) for i in range(2)]
+    ok = [(40, 10, 0, 0), (8, 2, 40, 40)]
+    expect(mics.MICS_ERR_INVALID_ARG, "not divisible", f, A, T + [T[0]], ok, 4, 3, 2, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "segment 1: numel", f, A, T, [(40, 10, 0, 0), (9, 2, 40, 40)], 4, 2, 2, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "overflow", f, A, T, [(40, 1 << 62, 0, 0)], 4, 2, 2, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "overlaps", f, A, [A + 64, T[1]], ok, 4, 2, 2, stream=0)
+    expect(mics.MICS_ERR_UNSUPPORTED, "elem_bytes", f, A, T, ok, 4, 2, 3, stream=0)
+    f(A, T, [], 4, 2, 2, stream=0)
+    f(A, T, [(0, 10, 0, 0)], 4, 2, 2, stream=0)
+    g = mics.mics_reduce_scatter_accum_coalesced
+    G = [A + BUF * (i + 1) for i in range(4)]
+    expect(mics.MICS_ERR_INVALID_ARG, "grads_bf16[3] is NULL", g, A, G[:3] + [None], [(8, 0, 0, 0)], False, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "overflow", g, A, G, [(1 << 61, 0, 0, 0)], False, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "overlaps", g, A, [G[0], A], [(8, 0, 8, 0)], False, stream=0)
+    expect(mics.MICS_ERR_ALIGNMENT, "acc", g, A + 1, G, [(8, 0, 0, 0)], False, stream=0)
+    g(A, G, [(0, 0, 5, 7)], True, stream=0)
 
 
 def test_launch_knob_range():

@@ -202,3 +202,63 @@ def test_group_view_full_size_h8192(orc, gen):
     # all p shards in one call: N_pad = 805,412,864 elements per launch, 25.8 GB of gradients
     cfg = gen.CONFIGS["h8192"]
     assert run_rank_pipeline(orc, gen, cfg, 0, cfg.N_pad, 0, n_windows=10) > 0
+
+
+def test_coalesced_layer_full_size_h8192(orc, gen):
+    """The h = 8192 layer as its 16 separately sharded tensors (biases of h/p = 512 elements next
+    to 4h^2-element matrices), rank view, through the coalesced entry points."""
+    cfg = gen.CONFIGS["h8192"]
+    p, k, s, rank = cfg.p, cfg.k, 2, 11
+    nodes = p // k
+    tb = Tables(gen, cfg)
+    lay = gen.coalesced_layout([n for _, n in gen.layer_tensors(8192)], p, k, align=8)
+    assert lay.shard_off[-1] == cfg.S and lay.flat_off[-1] == cfg.N
+    n_t = len(lay.S)
+
+    # reorder
+    T = [torch.empty(lay.stage1_off[-1], dtype=torch.int16, device=DEV) for _ in range(k)]
+    for t, St in enumerate(lay.S):
+        for g in range(p):
+            j, l = divmod(g, k)
+            at = lay.stage1_off[t] + j * St
+            tb.fill_dev(T[l][at:at + St], gen.stream_key(cfg.seed, gen.ROLE_PARAM, t, 0, g), 0, "param")
+    F = torch.full((cfg.N + 64,), 0x5A5A, dtype=torch.int16, device=DEV)
+    mics.mics_hier_gather_reorder_coalesced(F, T, lay.reorder_segments(), p, k, 2)
+    torch.cuda.synchronize()
+    assert bool((F[cfg.N:] == 0x5A5A).all())
+    for t in range(n_t):
+        St, n = lay.S[t], lay.numel[t]
+        wins = [(0, n)] if n <= 4 * WIN else windows(n, extra_points=[g * St for g in range(1, p)],
+                                                     seed=t, n_random=2)
+        for a, b in wins:
+            got = F[lay.flat_off[t] + a:lay.flat_off[t] + b].cpu().numpy().view(np.uint16)
+            parts, x = [], a
+            while x < b:
+                g, i = divmod(x, St)
+                m = min(b - x, St - i)
+                parts.append(tb.fill_host(gen.stream_key(cfg.seed, gen.ROLE_PARAM, t, 0, g), i, m, "param"))
+                x += m
+            assert np.array_equal(got, np.concatenate(parts)), (t, a, b)
+
+    # reduce-scatter-accumulate over full-length rank buffers
+    del T, F
+    grads = torch.empty((p, lay.grad_off[-1]), dtype=torch.int16, device=DEV)
+    acc = torch.full((cfg.S,), float("nan"), dtype=torch.float32, device=DEV)
+    segs = lay.reduce_segments(rank)
+    for ts in range(s):
+        for q in range(p):
+            tb.fill_dev(grads[q], grad_key(gen, cfg, 0, ts, q), 0, "grad")
+        mics.mics_reduce_scatter_accum_coalesced(acc, [grads[q] for q in range(p)], segs, ts > 0)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(acc).all())
+    for t in range(n_t):
+        St = lay.S[t]
+        wins = [(0, St)] if St <= 4 * WIN else windows(St, seed=100 + t, n_random=2)
+        for a, b in wins:
+            ref = np.empty(b - a, np.float32)
+            src0 = lay.grad_off[t] + rank * St + a
+            for ts in range(s):
+                host = [tb.fill_host(grad_key(gen, cfg, 0, ts, q), src0, b - a, "grad") for q in range(p)]
+                orc.reduce_scatter_accum(ref, host, 0, ts > 0)
+            got = acc[lay.shard_off[t] + a:lay.shard_off[t] + b].cpu().numpy()
+            assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), (t, a, b)

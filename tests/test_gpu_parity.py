@@ -309,3 +309,61 @@ def test_tiny_config_pipeline_and_shard_gather_invariant(orc, gen):
     assert bf16_ulp_distance(got, pb_ref[:N]).max() <= 1
     # and exactly the bf16 rounding of the HIP master shards laid end to end
     assert np.array_equal(got, orc.bf16_narrow(w_all)[:N])
+
+
+# ---- coalesced (per-tensor) forms --------------------------------------------------------------------
+
+COALESCED_CASES = [
+    # p, k, tensor sizes, shard alignment, elem_bytes
+    (4, 2, [4096, 64, 100000, 8, 33000], 8, 2),              # mixed sizes, all 16-byte clean
+    (16, 8, [512 * 16, 16 * 40000, 2048 * 16, 16 * 8], 8, 2),  # biases of h/p = 512 elements, p = 16
+    (8, 8, [1000, 77, 5000, 3], 1, 2),                        # odd shards: every tensor takes the slow path
+    (4, 2, [4096, 1001, 8192, 5], 8, 4),                      # fp32 elements, ragged tensors
+    (6, 3, [64 * 6] * 60, 8, 2),                              # more tensors than one launch carries
+]
+
+
+@pytest.mark.parametrize("p,k,numels,align,eb", COALESCED_CASES)
+def test_coalesced_reorder_is_bit_exact(orc, gen, p, k, numels, align, eb):
+    dtype = np.uint16 if eb == 2 else np.uint32
+    lay = gen.coalesced_layout(numels, p, k, align=align, flat_align=8 if align == 8 else 1)
+    nodes = p // k
+    shards = [[tagged(gen, 7000 + 100 * t + g, lay.S[t], dtype) for g in range(p)] for t in range(len(numels))]
+    T = [np.concatenate([np.concatenate([shards[t][j * k + l] for j in range(nodes)])
+                         for t in range(len(numels))]) for l in range(k)]
+    T_dev = [Guarded(t.size, dtype, fill=t) for t in T]
+    dst = Guarded(lay.flat_off[-1], dtype)
+    before = dst.numpy().copy()
+    mics.mics_hier_gather_reorder_coalesced(dst.t, [t.t for t in T_dev], lay.reorder_segments(), p, k, eb)
+    torch.cuda.synchronize()
+    want = before.copy()
+    orc.hier_gather_reorder_coalesced(T, lay.reorder_segments(), p, want)
+    assert np.array_equal(dst.numpy(), want)           # includes the untouched gaps between tensors
+    for t in range(len(numels)):                        # and the definition, tensor by tensor
+        got = dst.numpy()[lay.flat_off[t]:lay.flat_off[t] + numels[t]]
+        assert np.array_equal(got, orc.concat_shards(shards[t], numels[t]))
+    assert dst.guards_intact() and all(t.guards_intact() for t in T_dev)
+
+
+@pytest.mark.parametrize("p,k,numels,align", [
+    (4, 2, [4096, 64, 100000, 8, 33000], 8), (16, 8, [512 * 16, 16 * 40000, 2048 * 16, 16 * 8], 8),
+    (8, 8, [1000, 77, 5000, 3], 1), (32, 8, [32 * 1024, 32 * 8, 32 * 5000], 8), (3, 3, [30000, 24], 8),
+    (6, 3, [64 * 6] * 60, 8),
+])
+def test_coalesced_reduce_scatter_accum_is_bit_exact(orc, gen, p, k, numels, align):
+    lay = gen.coalesced_layout(numels, p, k, align=align)
+    tab = gen.normal_table(1e-3, "bf16")
+    total = lay.grad_off[-1]
+    for rank in (0, p - 1):
+        segs = lay.reduce_segments(rank)
+        acc = Guarded(lay.shard_off[-1], np.float32)
+        ref = np.full(lay.shard_off[-1], np.nan, np.float32)
+        for t_step in range(3):
+            host = [gen.fill_host(gen.stream_key(800, gen.ROLE_GRAD, 0, t_step, q), 0, total, tab)
+                    for q in range(p)]
+            dev = [Guarded(total, np.uint16, fill=h) for h in host]
+            mics.mics_reduce_scatter_accum_coalesced(acc.t, [d.t for d in dev], segs, t_step > 0)
+            torch.cuda.synchronize()
+            orc.reduce_scatter_accum_coalesced(ref, host, segs, t_step > 0)
+        assert np.array_equal(acc.numpy().view(np.uint32), ref.view(np.uint32))
+        assert acc.guards_intact()
