@@ -347,7 +347,9 @@ __device__ __forceinline__ float rsa_element(const PtrTable& g, int p, size_t x,
 // Partial sum over the p rank buffers of the 8 consecutive elements that start at element
 // `elem` (a multiple of 8 from 16-byte aligned bases), ranks in ascending order.  P > 0:
 // p = P known at compile time, all P loads issued before the first addition; P == 0: any p,
-// consumed in batches of 8 loads.
+// consumed in batches of 32 loads (a lane's additions are a serial chain, so the number of
+// load round trips per lane, p/32, is what a small message on a large group waits for: batches
+// of 8 put the floor of a p = 128 call at 25 us).
 template <int P, typename Tab>
 __device__ __forceinline__ void rsa_partial8(float (&s)[8], const Tab& g, int p, size_t elem)
 {
@@ -367,7 +369,7 @@ __device__ __forceinline__ void rsa_partial8(float (&s)[8], const Tab& g, int p,
             }
         }
     } else {
-        constexpr int B = 8;
+        constexpr int B = 32;
         {
             u32x4 first = ld<kRsaNtl>((const u32x4*)((const uint16_t*)g.ptr[0] + elem));
             #pragma unroll
@@ -715,6 +717,7 @@ int launch_reduce_scatter_accum(float* acc, const PtrTable& g, size_t count, int
             case 4: rsa_launch_fixed<4>(acc, g, nvec, accumulate, blocks, st); break;
             case 8: rsa_launch_fixed<8>(acc, g, nvec, accumulate, blocks, st); break;
             case 16: rsa_launch_fixed<16>(acc, g, nvec, accumulate, blocks, st); break;
+            case 32: rsa_launch_fixed<32>(acc, g, nvec, accumulate, blocks, st); break;
             default:
                 if (accumulate)
                     hipLaunchKernelGGL(rsa_vec_anyp_kernel<true>, dim3(blocks), dim3(kRsaBlock),
@@ -875,6 +878,7 @@ int launch_reduce_coalesced(float* acc, const PtrTable& g, const Segment* segs, 
             case 4: rsa_seg_launch<4>(acc, g, p, tab, (unsigned)tiles, accumulate, st); break;
             case 8: rsa_seg_launch<8>(acc, g, p, tab, (unsigned)tiles, accumulate, st); break;
             case 16: rsa_seg_launch<16>(acc, g, p, tab, (unsigned)tiles, accumulate, st); break;
+            case 32: rsa_seg_launch<32>(acc, g, p, tab, (unsigned)tiles, accumulate, st); break;
             default: rsa_seg_launch<0>(acc, g, p, tab, (unsigned)tiles, accumulate, st);
         }
         if (int e = launch_status()) return e;

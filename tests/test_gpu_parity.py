@@ -101,6 +101,8 @@ RSA_CASES = [
     (5, 30000, 16, 20001, 2, 0),
     (32, 20000, 160, 15000, 2, 0),            # cfg-4 group size
     (128, 4096, 0, 4096, 1, 0),               # largest group
+    (64, 40000, 64, 39000, 2, 0),             # 8 nodes of 8 (the paper's 50B-parameter group)
+    (40, 20000, 0, 20000, 2, 0),              # one full batch of 32 loads plus a partial one
     (4, 30000, 3, 20000, 2, 0),               # offset not a multiple of 8: element path
     (8, 30000, 0, 30000, 2, 1),               # buffers off 16-byte alignment: element path
 ]
