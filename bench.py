@@ -44,6 +44,9 @@ def parse_args():
                     help="treat the layer as its 16 separately sharded tensors (coalesced gather / "
                          "reduce-scatter): a1 and a2 run through the *_coalesced entry points on "
                          "full-length rank gradient buffers (4 sets, cycled over the micro-steps)")
+    ap.add_argument("--fused", action="store_true",
+                    help="run the replica average and the Adam step as one fused call "
+                         "(mics_replica_average_adam_shard): 4r+26 instead of 4r+34 bytes per element")
     ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -179,10 +182,16 @@ def main():
                 mics.mics_reduce_scatter_accum(acc, grad_tables[t], 0, count, t > 0, stream=sh)
         if timed:
             marks[2].record(stream)
-        mics.mics_replica_average(avg, copies, count, scale, stream=sh)
-        if timed:
-            marks[3].record(stream)
-        mics.mics_adam_shard(master, exp_avg, exp_avg_sq, param, avg, count, step=it, stream=sh, **hp)
+        if args.fused:
+            if timed:
+                marks[3].record(stream)
+            mics.mics_replica_average_adam_shard(master, exp_avg, exp_avg_sq, param, copies, count, scale,
+                                                 step=it, stream=sh, **hp)
+        else:
+            mics.mics_replica_average(avg, copies, count, scale, stream=sh)
+            if timed:
+                marks[3].record(stream)
+            mics.mics_adam_shard(master, exp_avg, exp_avg_sq, param, avg, count, step=it, stream=sh, **hp)
         if timed:
             marks[4].record(stream)
             all_marks.append(marks)
@@ -212,8 +221,8 @@ def main():
     b_a1 = 2 * 2 * N
     b_a2_first, b_a2_next = count * (2 * p + 4), count * (2 * p + 8)
     b_a2 = b_a2_first + (s - 1) * b_a2_next
-    b_a3 = count * (4 * r + 4)
-    b_a4 = count * 30
+    b_a3 = 0 if args.fused else count * (4 * r + 4)
+    b_a4 = count * (4 * r + 26) if args.fused else count * 30
     b_step = b_a1 + b_a2 + b_a3 + b_a4
     gbps = b_step / (ms_step * 1e-3) / 1e9
     a2_launch_ms = ms["a2"] / s
@@ -239,13 +248,14 @@ def main():
                         f"({nodes} nodes x k={k}), r={r}, s={s}, {args.view} view "
                         f"({count} elements per reduce/average/Adam call)"
                         + (", coalesced: 16 separately sharded tensors" if args.coalesced else ""),
-            "view": args.view, "coalesced": bool(args.coalesced), "N": N, "S": S, "p": p, "k": k, "r": r, "s": s,
+            "view": args.view, "coalesced": bool(args.coalesced), "fused_average_adam": bool(args.fused), "N": N, "S": S, "p": p, "k": k, "r": r, "s": s,
             "algorithmic_bytes_per_step": b_step,
         },
         "kernels": {
             name: {"ms": round(ms[name], 4),
                    "GB/s": round(b / (ms[name] * 1e-3) / 1e9, 1)}
             for name, b in (("a1", b_a1), ("a2", b_a2), ("a3", b_a3), ("a4", b_a4))
+            if not (args.fused and name == "a3")
         },
         "roofline": {
             "kernel": (f"rsa_seg_kernel<{p}> (mics_reduce_scatter_accum_coalesced)" if args.coalesced

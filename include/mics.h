@@ -160,6 +160,20 @@ int mics_adam_shard(float* master, float* exp_avg, float* exp_avg_sq,
                     float weight_decay, int step, void* stream);
 
 /*
+ * mics_replica_average followed by mics_adam_shard in one pass over the shard (Sections 3.4 and
+ * 2.1): the averaged gradient
+ *     g[x] = (((a_0[x] + a_1[x]) + ...) + a_{r-1}[x]) * scale
+ * is formed in registers and consumed by the Adam update at once, so it is never written to or
+ * re-read from memory.  Results (master, exp_avg, exp_avg_sq, param_bf16) are bit-identical to
+ * the two separate calls; the accumulator copies are only read.  Arguments as in those calls.
+ */
+int mics_replica_average_adam_shard(float* master, float* exp_avg, float* exp_avg_sq,
+                                    uint16_t* param_bf16, const float* const* acc_copies,
+                                    size_t count, int r, float scale, float lr, float beta1,
+                                    float beta2, float eps, float weight_decay, int step,
+                                    void* stream);
+
+/*
  * One separately sharded tensor of a coalesced call.  The paper's coalesced collectives
  * (Section 4, "Coalesced communication APIs": all_gather_coalesced, reduce_scatter_coalesced)
  * launch the per-tensor operations of many tensors at once, with no staging copy; the two

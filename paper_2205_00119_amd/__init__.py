@@ -25,6 +25,7 @@ EXPORTS = (
     "mics_version", "mics_last_error", "mics_shard_elems", "mics_set_blocks_per_cu",
     "mics_hier_gather_reorder", "mics_reduce_scatter_accum", "mics_replica_average",
     "mics_adam_shard", "mics_hier_gather_reorder_coalesced", "mics_reduce_scatter_accum_coalesced",
+    "mics_replica_average_adam_shard",
 )
 
 
@@ -77,6 +78,11 @@ lib.mics_hier_gather_reorder_coalesced.restype = _i
 lib.mics_reduce_scatter_accum_coalesced.argtypes = [_vp, _vp, ctypes.POINTER(mics_segment), _i, _i, _i,
                                                     _vp]
 lib.mics_reduce_scatter_accum_coalesced.restype = _i
+
+
+lib.mics_replica_average_adam_shard.argtypes = [_vp, _vp, _vp, _vp, _vp, _sz, _i, _f, _f, _f, _f, _f, _f,
+                                                _i, _vp]
+lib.mics_replica_average_adam_shard.restype = _i
 
 
 def _segments(segs) -> ctypes.Array:
@@ -179,3 +185,13 @@ def mics_reduce_scatter_accum_coalesced(acc, grads_bf16: Sequence, segs, accumul
     _check(lib.mics_reduce_scatter_accum_coalesced(_dev_ptr(acc), _table(grads_bf16), arr, len(arr),
                                                    len(grads_bf16), int(bool(accumulate)),
                                                    _stream(stream)))
+
+
+def mics_replica_average_adam_shard(master, exp_avg, exp_avg_sq, param_bf16, acc_copies: Sequence,
+                                    count: int, scale: float, *, lr: float, beta1: float, beta2: float,
+                                    eps: float, weight_decay: float, step: int, stream=None) -> None:
+    """Replica average and Adam step in one pass; same results as the two separate calls."""
+    _check(lib.mics_replica_average_adam_shard(
+        _dev_ptr(master), _dev_ptr(exp_avg), _dev_ptr(exp_avg_sq), _dev_ptr(param_bf16),
+        _table(acc_copies), count, len(acc_copies), scale, lr, beta1, beta2, eps, weight_decay, step,
+        _stream(stream)))

@@ -35,6 +35,18 @@ int hip_fail(const char* what, int err)
     return fail(MICS_ERR_HIP, "%s: HIP error %d (%s)", what, err, mics::hip_error_text(err));
 }
 
+mics::AdamScalars adam_scalars(float lr, float beta1, float beta2, float eps, float weight_decay,
+                               int step)
+{
+    mics::AdamScalars hp;
+    hp.lr = lr; hp.beta1 = beta1; hp.beta2 = beta2; hp.eps = eps; hp.weight_decay = weight_decay;
+    hp.one_minus_beta1 = 1.0f - beta1;
+    hp.one_minus_beta2 = 1.0f - beta2;
+    hp.bias_corr1 = (float)(1.0 - std::pow((double)beta1, (double)step));
+    hp.bias_corr2 = (float)(1.0 - std::pow((double)beta2, (double)step));
+    return hp;
+}
+
 }  // namespace
 
 extern "C" {
@@ -199,12 +211,7 @@ int mics_adam_shard(float* master, float* exp_avg, float* exp_avg_sq,
         vec16 = vec16 && aligned(param_bf16, 16);
     }
 
-    mics::AdamScalars hp;
-    hp.lr = lr; hp.beta1 = beta1; hp.beta2 = beta2; hp.eps = eps; hp.weight_decay = weight_decay;
-    hp.one_minus_beta1 = 1.0f - beta1;
-    hp.one_minus_beta2 = 1.0f - beta2;
-    hp.bias_corr1 = (float)(1.0 - std::pow((double)beta1, (double)step));
-    hp.bias_corr2 = (float)(1.0 - std::pow((double)beta2, (double)step));
+    const mics::AdamScalars hp = adam_scalars(lr, beta1, beta2, eps, weight_decay, step);
     int err = mics::launch_adam(master, exp_avg, exp_avg_sq, param_bf16, grad, count, hp, vec16,
                                 stream);
     return err ? hip_fail(fn, err) : MICS_OK;
@@ -360,6 +367,62 @@ int mics_reduce_scatter_accum_coalesced(float* acc, const uint16_t* const* grads
         }
     }
     return MICS_OK;
+}
+
+int mics_replica_average_adam_shard(float* master, float* exp_avg, float* exp_avg_sq,
+                                    uint16_t* param_bf16, const float* const* acc_copies,
+                                    size_t count, int r, float scale, float lr, float beta1,
+                                    float beta2, float eps, float weight_decay, int step,
+                                    void* stream)
+{
+    const char* fn = "mics_replica_average_adam_shard";
+    if (step < 1) return fail(MICS_ERR_INVALID_ARG, "%s: step = %d, must be >= 1", fn, step);
+    if (!(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f))
+        return fail(MICS_ERR_INVALID_ARG, "%s: beta1 = %g, beta2 = %g must lie in [0, 1)", fn,
+                    (double)beta1, (double)beta2);
+    if (r < 1 || r > MICS_MAX_GROUP)
+        return fail(MICS_ERR_INVALID_ARG, "%s: r = %d not in [1, %d]", fn, r, MICS_MAX_GROUP);
+    if (!acc_copies) return fail(MICS_ERR_INVALID_ARG, "%s: acc_copies is NULL", fn);
+    if (count > SIZE_MAX / 4) return fail(MICS_ERR_INVALID_ARG, "%s: count overflows", fn);
+    if (count == 0) return MICS_OK;
+    if (!master || !exp_avg || !exp_avg_sq)
+        return fail(MICS_ERR_INVALID_ARG, "%s: master, exp_avg and exp_avg_sq must be non-NULL", fn);
+    const void* st[3] = {master, exp_avg, exp_avg_sq};
+    const char* name[3] = {"master", "exp_avg", "exp_avg_sq"};
+    bool vec16 = true;
+    for (int a = 0; a < 3; ++a) {
+        if (!aligned(st[a], 4))
+            return fail(MICS_ERR_ALIGNMENT, "%s: %s not aligned to 4 bytes", fn, name[a]);
+        vec16 = vec16 && aligned(st[a], 16);
+        for (int b = a + 1; b < 3; ++b)
+            if (overlaps(st[a], count * 4, st[b], count * 4))
+                return fail(MICS_ERR_INVALID_ARG, "%s: %s overlaps %s", fn, name[a], name[b]);
+        if (param_bf16 && overlaps(st[a], count * 4, param_bf16, count * 2))
+            return fail(MICS_ERR_INVALID_ARG, "%s: param_bf16 overlaps %s", fn, name[a]);
+    }
+    if (param_bf16) {
+        if (!aligned(param_bf16, 2))
+            return fail(MICS_ERR_ALIGNMENT, "%s: param_bf16 not aligned to 2 bytes", fn);
+        vec16 = vec16 && aligned(param_bf16, 16);
+    }
+    mics::PtrTable tab{};
+    for (int c = 0; c < r; ++c) {
+        const float* a = acc_copies[c];
+        if (!a) return fail(MICS_ERR_INVALID_ARG, "%s: acc_copies[%d] is NULL", fn, c);
+        if (!aligned(a, 4))
+            return fail(MICS_ERR_ALIGNMENT, "%s: acc_copies[%d] not aligned to 4 bytes", fn, c);
+        for (int b = 0; b < 3; ++b)
+            if (overlaps(st[b], count * 4, a, count * 4))
+                return fail(MICS_ERR_INVALID_ARG, "%s: %s overlaps acc_copies[%d]", fn, name[b], c);
+        if (param_bf16 && overlaps(param_bf16, count * 2, a, count * 4))
+            return fail(MICS_ERR_INVALID_ARG, "%s: param_bf16 overlaps acc_copies[%d]", fn, c);
+        vec16 = vec16 && aligned(a, 16);
+        tab.ptr[c] = a;
+    }
+    const mics::AdamScalars hp = adam_scalars(lr, beta1, beta2, eps, weight_decay, step);
+    int err = mics::launch_avg_adam(master, exp_avg, exp_avg_sq, param_bf16, tab, r, scale, count, hp,
+                                    vec16, stream);
+    return err ? hip_fail(fn, err) : MICS_OK;
 }
 
 }  // extern "C"

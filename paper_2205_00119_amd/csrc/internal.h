@@ -40,6 +40,11 @@ int launch_adam(float* master, float* exp_avg, float* exp_avg_sq,
                 uint16_t* param_bf16, const float* grad, size_t count,
                 const AdamScalars& hp, bool vec16, void* stream);
 
+// Replica average and Adam in one pass (the averaged gradient stays in registers).
+int launch_avg_adam(float* master, float* exp_avg, float* exp_avg_sq, uint16_t* param_bf16,
+                    const PtrTable& copies, int r, float scale, size_t count, const AdamScalars& hp,
+                    bool vec16, void* stream);
+
 // Segment records travel in the kernel-argument segment: at most this many per launch.
 constexpr int kMaxSegPerLaunch = 48;
 

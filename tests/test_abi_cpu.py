@@ -23,7 +23,7 @@ def declared_functions():
 
 def test_library_exports_every_declared_function():
     names = declared_functions()
-    assert len(names) >= 10
+    assert len(names) >= 11
     for name in names:
         assert hasattr(mics.lib, name), f"{name} declared in mics.h but not exported"
     assert sorted(set(names)) == sorted(mics.EXPORTS)
@@ -123,6 +123,20 @@ def test_coalesced_argument_errors():
     expect(mics.MICS_ERR_INVALID_ARG, "overlaps", g, A, [G[0], A], [(8, 0, 8, 0)], False, stream=0)
     expect(mics.MICS_ERR_ALIGNMENT, "acc", g, A + 1, G, [(8, 0, 0, 0)], False, stream=0)
     g(A, G, [(0, 0, 5, 7)], True, stream=0)
+
+
+def test_fused_average_adam_argument_errors():
+    f = mics.mics_replica_average_adam_shard
+    w, m, v, pb = (A + BUF * i for i in range(4))
+    C = [A + BUF * (5 + i) for i in range(3)]
+    hp = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0)
+    expect(mics.MICS_ERR_INVALID_ARG, "step = 0", f, w, m, v, pb, C, 8, 0.5, step=0, stream=0, **hp)
+    expect(mics.MICS_ERR_INVALID_ARG, "r = 0", f, w, m, v, pb, [], 8, 0.5, step=1, stream=0, **hp)
+    expect(mics.MICS_ERR_INVALID_ARG, "acc_copies[2] is NULL", f, w, m, v, pb, C[:2] + [None], 8, 0.5, step=1, stream=0, **hp)
+    expect(mics.MICS_ERR_INVALID_ARG, "exp_avg overlaps acc_copies[1]", f, w, m, v, pb, [C[0], m + 4], 8, 0.5, step=1, stream=0, **hp)
+    expect(mics.MICS_ERR_ALIGNMENT, "acc_copies[0]", f, w, m, v, pb, [C[0] + 2], 8, 0.5, step=1, stream=0, **hp)
+    expect(mics.MICS_ERR_INVALID_ARG, "non-NULL", f, None, m, v, pb, C, 8, 0.5, step=1, stream=0, **hp)
+    f(w, m, v, pb, C, 0, 0.5, step=1, stream=0, **hp)
 
 
 def test_launch_knob_range():

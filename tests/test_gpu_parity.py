@@ -369,3 +369,51 @@ def test_coalesced_reduce_scatter_accum_is_bit_exact(orc, gen, p, k, numels, ali
             orc.reduce_scatter_accum_coalesced(ref, host, segs, t_step > 0)
         assert np.array_equal(acc.numpy().view(np.uint32), ref.view(np.uint32))
         assert acc.guards_intact()
+
+
+# ---- fused replica average + Adam -------------------------------------------------------------------
+
+@pytest.mark.parametrize("r,count,skew,want_bf16", [
+    (8, 3 * 2048 * 4 + 7, 0, True), (2, 40000, 0, True), (1, 5000, 0, False), (3, 20001, 0, True),
+    (16, 9000, 0, True), (4, 30000, 1, True), (8, 3, 0, True),
+])
+def test_fused_average_adam_equals_the_two_separate_calls_and_the_oracle(orc, gen, r, count, skew, want_bf16):
+    hp = dict(HP, weight_decay=0.01)
+    scale = float(np.float32(1.0 / (r * 16 * 12)))
+    tab = gen.normal_table(1e-4 * (16 * 12) ** 0.5, "f32")
+    copies_h = [gen.fill_host(gen.stream_key(900, gen.ROLE_ACC, c), 0, count, tab) for c in range(r)]
+    copies = [Guarded(count, np.float32, skew=skew, fill=h) for h in copies_h]
+    w0 = gen.fill_host(gen.stream_key(900, gen.ROLE_MASTER), 0, count, gen.normal_table(0.02, "f32"))
+    zeros = np.zeros(count, np.float32)
+    fused = [Guarded(count, np.float32, skew=skew, fill=x) for x in (w0, zeros, zeros)]
+    split = [Guarded(count, np.float32, skew=skew, fill=x) for x in (w0, zeros, zeros)]
+    pb_f = Guarded(count, np.uint16, skew=skew) if want_bf16 else None
+    pb_s = Guarded(count, np.uint16, skew=skew) if want_bf16 else None
+    avg = Guarded(count, np.float32, skew=skew)
+    wr, mr, vr = w0.copy(), zeros.copy(), zeros.copy()
+    for step in (1, 2):
+        mics.mics_replica_average_adam_shard(fused[0].t, fused[1].t, fused[2].t, pb_f.t if pb_f else None,
+                                             [c.t for c in copies], count, scale, step=step, **hp)
+        mics.mics_replica_average(avg.t, [c.t for c in copies], count, scale)
+        mics.mics_adam_shard(split[0].t, split[1].t, split[2].t, pb_s.t if pb_s else None, avg.t, count,
+                             step=step, **hp)
+        torch.cuda.synchronize()
+        w_prev = wr.copy()
+        pbr = orc.adam_shard(wr, mr, vr, orc.replica_average(copies_h, scale), step=step, f32=True, **hp)
+        for a, b, ref in zip(fused, split, (wr, mr, vr)):
+            assert np.array_equal(a.numpy().view(np.uint32), b.numpy().view(np.uint32))
+            assert np.array_equal(a.numpy().view(np.uint32), ref.view(np.uint32))
+        if pb_f:
+            assert np.array_equal(pb_f.numpy(), pb_s.numpy()) and np.array_equal(pb_f.numpy(), pbr)
+    # against the double-precision oracle from the start, two steps
+    w64, m64, v64 = w0.copy(), zeros.copy(), zeros.copy()
+    g64 = orc.replica_average(copies_h, scale)
+    for step in (1, 2):
+        before = w64.copy()
+        pb64 = orc.adam_shard(w64, m64, v64, g64, step=step, **hp)
+    assert adam_rel_err(fused[0].numpy(), w64, before).max() <= 2e-6      # two steps of drift
+    if pb_f:
+        assert bf16_ulp_distance(pb_f.numpy(), pb64).max() <= 1
+    assert all(x.guards_intact() for x in fused + copies) and (pb_f is None or pb_f.guards_intact())
+    for c, h in zip(copies, copies_h):
+        assert np.array_equal(c.numpy(), h), "an accumulator copy was modified"
