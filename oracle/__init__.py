@@ -56,6 +56,9 @@ def _load():
         lib.orc_hier_gather_reorder.argtypes = [vp, vp, sz, sz, i32, i32, i32]
         lib.orc_reduce_scatter_accum.argtypes = [vp, vp, sz, sz, i32, i32]
         lib.orc_reduce_scatter_accum_f64.argtypes = [vp, vp, sz, sz, i32, i32]
+        lib.orc_reduce_scatter_accum_typed.argtypes = [vp, vp, sz, sz, i32, i32, i32]
+        lib.orc_f16_widen_array.argtypes = [vp, vp, sz]
+        lib.orc_f16_widen_array.restype = None
         lib.orc_replica_average.argtypes = [vp, vp, sz, i32, f32]
         adam = [vp, vp, vp, vp, vp, sz, f32, f32, f32, f32, f32, i32]
         lib.orc_adam_shard.argtypes = adam
@@ -181,6 +184,32 @@ def reduce_scatter_accum_coalesced(acc, grads: Sequence[np.ndarray], segs, accum
     acc = _c(acc, np.float32)
     for count, _, src_off, dst_off in segs:
         reduce_scatter_accum(acc[dst_off:dst_off + count], grads, src_off, accumulate)
+    return acc
+
+
+DTYPE_BF16, DTYPE_F16, DTYPE_F32 = 0, 1, 2
+
+
+def f16_widen(h) -> np.ndarray:
+    """IEEE binary16 bit patterns (uint16) -> float32, exact."""
+    h = np.ascontiguousarray(h, dtype=np.uint16)
+    out = np.empty(h.shape, dtype=np.float32)
+    _load().orc_f16_widen_array(_ptr(out), _ptr(h), h.size)
+    return out
+
+
+def reduce_scatter_accum_typed(acc, grads: Sequence[np.ndarray], elem_offset: int, accumulate: bool,
+                               dtype: int) -> np.ndarray:
+    """reduce_scatter_accum for gradients stored as bf16 / binary16 bit patterns (uint16 arrays)
+    or as float32 arrays; in place on ``acc`` (float32)."""
+    acc = _c(acc, np.float32)
+    want = np.float32 if dtype == DTYPE_F32 else np.uint16
+    grads = [_c(g, want) for g in grads]
+    if any(g.size < elem_offset + acc.size for g in grads):
+        raise ValueError("gradient buffer shorter than elem_offset + count")
+    _check(_load().orc_reduce_scatter_accum_typed(_ptr(acc), _table(grads), elem_offset, acc.size,
+                                                  len(grads), int(bool(accumulate)), dtype),
+           "reduce_scatter_accum_typed")
     return acc
 
 

@@ -68,6 +68,36 @@ void orc_bf16_widen_array(float* out, const uint16_t* in, size_t n)
     for (size_t i = 0; i < n; ++i) out[i] = orc_bf16_widen(in[i]);
 }
 
+/* IEEE-754 binary16 -> binary32, exact (every binary16 value is a binary32 value). */
+float orc_f16_widen(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    uint32_t exp = (h >> 10) & 0x1Fu;
+    uint32_t frac = h & 0x3FFu;
+    uint32_t u;
+    if (exp == 0x1Fu) {
+        u = sign | 0x7F800000u | (frac << 13);               /* Inf or NaN */
+    } else if (exp != 0) {
+        u = sign | ((exp - 15 + 127) << 23) | (frac << 13);  /* normal */
+    } else if (frac == 0) {
+        u = sign;                                            /* zero */
+    } else {
+        /* subnormal: frac * 2^-24; normalise */
+        int shift = 0;
+        while (!(frac & 0x400u)) { frac <<= 1; ++shift; }
+        frac &= 0x3FFu;
+        u = sign | ((uint32_t)(127 - 15 + 1 - shift) << 23) | (frac << 13);
+    }
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+void orc_f16_widen_array(float* out, const uint16_t* in, size_t n)
+{
+    for (size_t i = 0; i < n; ++i) out[i] = orc_f16_widen(in[i]);
+}
+
 /* ---- hierarchical all-gather (Section 3.3) ------------------------------- */
 
 static int geometry_ok(int p, int k, int elem_bytes)
@@ -166,6 +196,35 @@ int orc_reduce_scatter_accum(float* acc, const uint16_t* const* grads,
         float partial = orc_bf16_widen(grads[0][x]);
         for (int q = 1; q < p; ++q) {
             float gq = orc_bf16_widen(grads[q][x]);
+            partial = partial + gq;
+        }
+        float before = accumulate ? acc[i] : 0.0f;
+        acc[i] = before + partial;
+    }
+    return 0;
+}
+
+static float widen_grad(const void* buf, size_t x, int dtype)
+{
+    if (dtype == ORC_DTYPE_F32) return ((const float*)buf)[x];
+    if (dtype == ORC_DTYPE_F16) return orc_f16_widen(((const uint16_t*)buf)[x]);
+    return orc_bf16_widen(((const uint16_t*)buf)[x]);
+}
+
+int orc_reduce_scatter_accum_typed(float* acc, const void* const* grads,
+                                   size_t elem_offset, size_t count, int p,
+                                   int accumulate, int dtype)
+{
+    if (p < 1 || !grads) return -1;
+    if (dtype != ORC_DTYPE_BF16 && dtype != ORC_DTYPE_F16 && dtype != ORC_DTYPE_F32) return -1;
+    if (count && !acc) return -1;
+    for (int q = 0; q < p; ++q) if (!grads[q]) return -1;
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+    for (size_t i = 0; i < count; ++i) {
+        size_t x = elem_offset + i;
+        float partial = widen_grad(grads[0], x, dtype);
+        for (int q = 1; q < p; ++q) {
+            float gq = widen_grad(grads[q], x, dtype);
             partial = partial + gq;
         }
         float before = accumulate ? acc[i] : 0.0f;

@@ -78,6 +78,19 @@ int orc_reduce_scatter_accum(float* acc, const uint16_t* const* grads,
                              size_t elem_offset, size_t count, int p,
                              int accumulate);
 
+/* The same reduction for gradients stored as bf16, IEEE binary16 or binary32 (the paper trains
+ * in mixed precision on V100, which has no bf16, and one model in plain float32, Section 5).
+ * Widening to binary32 is exact for all three; a loss scale, if any, is undone by the scale
+ * of orc_replica_average. */
+#define ORC_DTYPE_BF16 0
+#define ORC_DTYPE_F16  1
+#define ORC_DTYPE_F32  2
+int orc_reduce_scatter_accum_typed(float* acc, const void* const* grads,
+                                   size_t elem_offset, size_t count, int p,
+                                   int accumulate, int dtype);
+float orc_f16_widen(uint16_t h);
+void  orc_f16_widen_array(float* out, const uint16_t* in, size_t n);
+
 /* Same sum carried in binary64 (every bf16 value and every partial is exact
  * or nearly so): the yardstick that bounds the binary32 error. */
 int orc_reduce_scatter_accum_f64(double* acc, const uint16_t* const* grads,
