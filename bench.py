@@ -44,6 +44,9 @@ def parse_args():
                     help="treat the layer as its 16 separately sharded tensors (coalesced gather / "
                          "reduce-scatter): a1 and a2 run through the *_coalesced entry points on "
                          "full-length rank gradient buffers (4 sets, cycled over the micro-steps)")
+    ap.add_argument("--grad-dtype", choices=["bf16", "f16", "f32"], default="bf16",
+                    help="storage format of the gradient buffers the reduce-scatter-accumulate reads "
+                         "(rank view, flat layout)")
     ap.add_argument("--fused", action="store_true",
                     help="run the replica average and the Adam step as one fused call "
                          "(mics_replica_average_adam_shard): 4r+26 instead of 4r+34 bytes per element")
@@ -113,11 +116,26 @@ def main():
 
         # a2: per micro-step, p gradient buffers covering the elements this call owns
         n_sets = 1 if group else s
-        grads = torch.empty((n_sets, p, count), dtype=torch.int16, device=dev)
+        if args.grad_dtype == "bf16":
+            grads = torch.empty((n_sets, p, count), dtype=torch.int16, device=dev)
+            g_tab, g_out, g_bytes = tab_g, tab_go, 2
+        elif args.grad_dtype == "f16":
+            grads = torch.empty((n_sets, p, count), dtype=torch.int16, device=dev)
+            as_f16 = lambda sig: torch.from_numpy(
+                synth.normal_table(sig, "f32").astype(np.float16).view(np.int16)).to(dev)
+            g_tab = as_f16(cfg.sigma_grad * 1024)          # loss-scaled by 2^10
+            g_out = as_f16(cfg.sigma_grad * 1024 * cfg.outlier_scale) if cfg.outlier_frac else None
+            g_bytes = 2
+        else:
+            grads = torch.empty((n_sets, p, count), dtype=torch.float32, device=dev)
+            g_tab = torch.from_numpy(synth.normal_table(cfg.sigma_grad, "f32")).to(dev)
+            g_out = (torch.from_numpy(synth.normal_table(cfg.sigma_grad * cfg.outlier_scale, "f32")).to(dev)
+                     if cfg.outlier_frac else None)
+            g_bytes = 4
         for t in range(n_sets):
             for q in range(p):
-                fill(grads[t, q], synth.stream_key(cfg.seed, synth.ROLE_GRAD, 0, t, q), offset, tab_g, 2,
-                     tab_go, cfg.outlier_frac)
+                fill(grads[t, q], synth.stream_key(cfg.seed, synth.ROLE_GRAD, 0, t, q), offset, g_tab, g_bytes,
+                     g_out, cfg.outlier_frac)
         grad_tables = [[grads[t % n_sets, q] for q in range(p)] for t in range(s)]
     else:
         if group or cfg.name == "tiny" or cfg.align != 8:
@@ -162,6 +180,11 @@ def main():
     hp = dict(lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps, weight_decay=cfg.weight_decay)
     torch.cuda.synchronize()
 
+    grad_code = {"bf16": mics.MICS_DTYPE_BF16, "f16": mics.MICS_DTYPE_F16, "f32": mics.MICS_DTYPE_F32}[args.grad_dtype]
+    gb = 4 if args.grad_dtype == "f32" else 2
+    if args.grad_dtype != "bf16" and args.coalesced:
+        print("--grad-dtype other than bf16 is for the flat layout", file=sys.stderr)
+        sys.exit(2)
     ev = {name: [] for name in ("a1", "a2", "a3", "a4")}
     all_marks = []
 
@@ -178,6 +201,8 @@ def main():
         for t in range(s):
             if args.coalesced:
                 mics.mics_reduce_scatter_accum_coalesced(acc, grad_tables[t], reduce_segs, t > 0, stream=sh)
+            elif args.grad_dtype != "bf16":
+                mics.mics_reduce_scatter_accum_typed(acc, grad_tables[t], 0, count, t > 0, grad_code, stream=sh)
             else:
                 mics.mics_reduce_scatter_accum(acc, grad_tables[t], 0, count, t > 0, stream=sh)
         if timed:
@@ -219,7 +244,7 @@ def main():
 
     # ---- algorithmic bytes (what the method must move) ---------------------------------------
     b_a1 = 2 * 2 * N
-    b_a2_first, b_a2_next = count * (2 * p + 4), count * (2 * p + 8)
+    b_a2_first, b_a2_next = count * (gb * p + 4), count * (gb * p + 8)
     b_a2 = b_a2_first + (s - 1) * b_a2_next
     b_a3 = 0 if args.fused else count * (4 * r + 4)
     b_a4 = count * (4 * r + 26) if args.fused else count * 30
@@ -239,7 +264,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16 in / f32 accumulate",
+        "dtype": f"{args.grad_dtype} in / f32 accumulate",
         "data": "synthetic",
         "pct_of_peak_hbm": round(100.0 * gbps / PEAK_HBM_GBPS, 2),
         "elements_per_s": round(count / (ms_step * 1e-3), 1),
@@ -259,7 +284,8 @@ def main():
         },
         "roofline": {
             "kernel": (f"rsa_seg_kernel<{p}> (mics_reduce_scatter_accum_coalesced)" if args.coalesced
-                       else f"rsa_vec_kernel<{p}> (mics_reduce_scatter_accum)"),
+                       else f"rsa_vec_kernel<{p}> (mics_reduce_scatter_accum)" if args.grad_dtype == "bf16"
+                       else f"rsa_typed_vec_kernel<{args.grad_dtype},{p}> (mics_reduce_scatter_accum_typed)"),
             "bound": "hbm",
             "achieved": round(a2_gbps, 1),
             "peak": PEAK_HBM_GBPS,
@@ -267,7 +293,8 @@ def main():
             "frac": round(a2_gbps / PEAK_HBM_GBPS, 4),
             "avg_launch_ms": round(a2_launch_ms, 5),
             "algorithmic_bytes_per_launch": b_a2 // s,
-            "traffic": None if args.coalesced else MEASURED_TRAFFIC.get((cfg.name, args.view)),
+            "traffic": (None if args.coalesced or args.grad_dtype != "bf16"
+                        else MEASURED_TRAFFIC.get((cfg.name, args.view))),
         },
     }
     if not args.no_cpu_baseline:

@@ -122,6 +122,21 @@ int mics_reduce_scatter_accum(float* acc, const uint16_t* const* grads_bf16,
                               int accumulate, void* stream);
 
 /*
+ * mics_reduce_scatter_accum for gradients stored in another format.  The paper's runs use
+ * "mixed-precision" on V100 GPUs, which have no bf16 (Section 5), and one model in plain
+ * float32 (the WideResNet experiment): grad_dtype selects bf16 (as above), IEEE binary16 or
+ * binary32 buffers.  Widening to binary32 is exact in all three, the additions and their order
+ * are the same.  A loss scale applied to binary16 gradients is undone by folding 1/loss_scale
+ * into the `scale` of mics_replica_average.  grads: host table of p device pointers.
+ */
+#define MICS_DTYPE_BF16 0
+#define MICS_DTYPE_F16  1
+#define MICS_DTYPE_F32  2
+int mics_reduce_scatter_accum_typed(float* acc, const void* const* grads, size_t elem_offset,
+                                    size_t count, int p, int accumulate, int grad_dtype,
+                                    void* stream);
+
+/*
  * Hop 2 (Section 3.4): the reduction of the all-reduce inside the replication
  * group at the gradient-accumulation boundary, and the single scaling that
  * turns the sums of both hops into the global-batch mean:

@@ -25,8 +25,9 @@ EXPORTS = (
     "mics_version", "mics_last_error", "mics_shard_elems", "mics_set_blocks_per_cu",
     "mics_hier_gather_reorder", "mics_reduce_scatter_accum", "mics_replica_average",
     "mics_adam_shard", "mics_hier_gather_reorder_coalesced", "mics_reduce_scatter_accum_coalesced",
-    "mics_replica_average_adam_shard",
+    "mics_replica_average_adam_shard", "mics_reduce_scatter_accum_typed",
 )
+MICS_DTYPE_BF16, MICS_DTYPE_F16, MICS_DTYPE_F32 = 0, 1, 2
 
 
 class MicsError(RuntimeError):
@@ -83,6 +84,10 @@ lib.mics_reduce_scatter_accum_coalesced.restype = _i
 lib.mics_replica_average_adam_shard.argtypes = [_vp, _vp, _vp, _vp, _vp, _sz, _i, _f, _f, _f, _f, _f, _f,
                                                 _i, _vp]
 lib.mics_replica_average_adam_shard.restype = _i
+
+
+lib.mics_reduce_scatter_accum_typed.argtypes = [_vp, _vp, _sz, _sz, _i, _i, _i, _vp]
+lib.mics_reduce_scatter_accum_typed.restype = _i
 
 
 def _segments(segs) -> ctypes.Array:
@@ -195,3 +200,11 @@ def mics_replica_average_adam_shard(master, exp_avg, exp_avg_sq, param_bf16, acc
         _dev_ptr(master), _dev_ptr(exp_avg), _dev_ptr(exp_avg_sq), _dev_ptr(param_bf16),
         _table(acc_copies), count, len(acc_copies), scale, lr, beta1, beta2, eps, weight_decay, step,
         _stream(stream)))
+
+
+def mics_reduce_scatter_accum_typed(acc, grads: Sequence, elem_offset: int, count: int,
+                                    accumulate: bool, grad_dtype: int, stream=None) -> None:
+    """mics_reduce_scatter_accum for bf16 / fp16 / fp32 gradient buffers (MICS_DTYPE_*)."""
+    _check(lib.mics_reduce_scatter_accum_typed(_dev_ptr(acc), _table(grads), elem_offset, count,
+                                               len(grads), int(bool(accumulate)), grad_dtype,
+                                               _stream(stream)))

@@ -116,14 +116,17 @@ int mics_hier_gather_reorder(void* dst_flat, const void* const* stage1_bufs,
     return err ? hip_fail(fn, err) : MICS_OK;
 }
 
-int mics_reduce_scatter_accum(float* acc, const uint16_t* const* grads_bf16,
-                              size_t elem_offset, size_t count, int p,
-                              int accumulate, void* stream)
+int mics_reduce_scatter_accum_typed(float* acc, const void* const* grads, size_t elem_offset,
+                                    size_t count, int p, int accumulate, int grad_dtype,
+                                    void* stream)
 {
     const char* fn = "mics_reduce_scatter_accum";
+    if (grad_dtype != MICS_DTYPE_BF16 && grad_dtype != MICS_DTYPE_F16 && grad_dtype != MICS_DTYPE_F32)
+        return fail(MICS_ERR_UNSUPPORTED, "%s: grad_dtype = %d is not bf16, f16 or f32", fn, grad_dtype);
+    const size_t gb = grad_dtype == MICS_DTYPE_F32 ? 4 : 2;
     if (p < 1 || p > MICS_MAX_GROUP)
         return fail(MICS_ERR_INVALID_ARG, "%s: p = %d not in [1, %d]", fn, p, MICS_MAX_GROUP);
-    if (!grads_bf16) return fail(MICS_ERR_INVALID_ARG, "%s: grads_bf16 is NULL", fn);
+    if (!grads) return fail(MICS_ERR_INVALID_ARG, "%s: the gradient table is NULL", fn);
     if (elem_offset > SIZE_MAX / 4 - count || count > SIZE_MAX / 4)
         return fail(MICS_ERR_INVALID_ARG, "%s: elem_offset + count overflows", fn);
     if (count == 0) return MICS_OK;
@@ -133,18 +136,29 @@ int mics_reduce_scatter_accum(float* acc, const uint16_t* const* grads_bf16,
     mics::PtrTable tab{};
     bool vec16 = aligned(acc, 16);
     for (int q = 0; q < p; ++q) {
-        const uint16_t* g = grads_bf16[q];
+        const void* g = grads[q];
         if (!g) return fail(MICS_ERR_INVALID_ARG, "%s: grads_bf16[%d] is NULL", fn, q);
-        if (!aligned(g, 2))
-            return fail(MICS_ERR_ALIGNMENT, "%s: grads_bf16[%d] not aligned to 2 bytes", fn, q);
-        const uint16_t* first = g + elem_offset;
-        if (overlaps(acc, count * 4, first, count * 2))
+        if (!aligned(g, gb))
+            return fail(MICS_ERR_ALIGNMENT, "%s: grads_bf16[%d] not aligned to %zu bytes", fn, q, gb);
+        const char* first = (const char*)g + elem_offset * gb;
+        if (overlaps(acc, count * 4, first, count * gb))
             return fail(MICS_ERR_INVALID_ARG, "%s: acc overlaps grads_bf16[%d]", fn, q);
         vec16 = vec16 && aligned(first, 16);
         tab.ptr[q] = first;
     }
-    int err = mics::launch_reduce_scatter_accum(acc, tab, count, p, accumulate != 0, vec16, stream);
+    int err = grad_dtype == MICS_DTYPE_BF16
+                  ? mics::launch_reduce_scatter_accum(acc, tab, count, p, accumulate != 0, vec16, stream)
+                  : mics::launch_reduce_scatter_accum_typed(acc, tab, count, p, accumulate != 0,
+                                                            grad_dtype, vec16, stream);
     return err ? hip_fail(fn, err) : MICS_OK;
+}
+
+int mics_reduce_scatter_accum(float* acc, const uint16_t* const* grads_bf16,
+                              size_t elem_offset, size_t count, int p,
+                              int accumulate, void* stream)
+{
+    return mics_reduce_scatter_accum_typed(acc, (const void* const*)grads_bf16, elem_offset, count, p,
+                                           accumulate, MICS_DTYPE_BF16, stream);
 }
 
 int mics_replica_average(float* out, const float* const* acc_copies,

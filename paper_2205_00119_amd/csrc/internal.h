@@ -40,6 +40,10 @@ int launch_adam(float* master, float* exp_avg, float* exp_avg_sq,
                 uint16_t* param_bf16, const float* grad, size_t count,
                 const AdamScalars& hp, bool vec16, void* stream);
 
+// kind 1: IEEE binary16 gradients, kind 2: binary32 gradients (bf16 has its own launcher).
+int launch_reduce_scatter_accum_typed(float* acc, const PtrTable& grads, size_t count, int p,
+                                      bool accumulate, int kind, bool vec16, void* stream);
+
 // Replica average and Adam in one pass (the averaged gradient stays in registers).
 int launch_avg_adam(float* master, float* exp_avg, float* exp_avg_sq, uint16_t* param_bf16,
                     const PtrTable& copies, int r, float scale, size_t count, const AdamScalars& hp,

@@ -462,6 +462,99 @@ __global__ __launch_bounds__(kRsaBlock) void rsa_seg_kernel(
     }
 }
 
+// Gradients stored as IEEE binary16 (KIND 1: what mixed precision means on GPUs without bf16)
+// or binary32 (KIND 2: plain float32 training).  Same reduction, same order; widening is exact.
+// A lane owns one 128-bit vector per rank buffer: 8 binary16 or 4 binary32 elements.
+
+template <int KIND>
+__device__ __forceinline__ void widen_vec(float (&out)[8], u32x4 v)
+{
+    if constexpr (KIND == 1) {
+        #pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t pair = v[e];
+            out[2 * e] = (float)__builtin_bit_cast(_Float16, (uint16_t)(pair & 0xFFFFu));
+            out[2 * e + 1] = (float)__builtin_bit_cast(_Float16, (uint16_t)(pair >> 16));
+        }
+    } else {
+        #pragma unroll
+        for (int e = 0; e < 4; ++e) out[e] = __uint_as_float(v[e]);
+    }
+}
+
+template <int KIND>
+__device__ __forceinline__ float widen_one(const void* buf, size_t x)
+{
+    if constexpr (KIND == 1) return (float)((const _Float16*)buf)[x];
+    else return ((const float*)buf)[x];
+}
+
+template <int KIND, int P, bool ACCUM, typename Tab>
+__global__ __launch_bounds__(kRsaBlock) void rsa_typed_vec_kernel(
+    float* __restrict__ acc, Tab g, int p, size_t nvec)
+{
+    constexpr int EPV = KIND == 1 ? 8 : 4;     // elements per 128-bit vector
+    const size_t stride = (size_t)gridDim.x * kRsaBlock;
+    for (size_t i = (size_t)blockIdx.x * kRsaBlock + threadIdx.x; i < nvec; i += stride) {
+        float a[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+        if (ACCUM) {
+            #pragma unroll
+            for (int h = 0; h < EPV / 4; ++h) {
+                const f32x4 t = ld<kRsaNtl>((const f32x4*)acc + (EPV / 4) * i + h);
+                a[4 * h] = t.x; a[4 * h + 1] = t.y; a[4 * h + 2] = t.z; a[4 * h + 3] = t.w;
+            }
+        }
+        float s[8], w[8];
+        if constexpr (P > 0) {
+            u32x4 v[P];
+            #pragma unroll
+            for (int q = 0; q < P; ++q) v[q] = ld<kRsaNtl>((const u32x4*)g.ptr[q] + i);
+            widen_vec<KIND>(s, v[0]);
+            #pragma unroll
+            for (int q = 1; q < P; ++q) {
+                widen_vec<KIND>(w, v[q]);
+                #pragma unroll
+                for (int e = 0; e < EPV; ++e) s[e] = s[e] + w[e];
+            }
+        } else {
+            constexpr int B = 32;
+            widen_vec<KIND>(s, ld<kRsaNtl>((const u32x4*)g.ptr[0] + i));
+            for (int q0 = 1; q0 < p; q0 += B) {
+                u32x4 v[B];
+                #pragma unroll
+                for (int b = 0; b < B; ++b)
+                    if (q0 + b < p) v[b] = ld<kRsaNtl>((const u32x4*)g.ptr[q0 + b] + i);
+                #pragma unroll
+                for (int b = 0; b < B; ++b) {
+                    if (q0 + b < p) {
+                        widen_vec<KIND>(w, v[b]);
+                        #pragma unroll
+                        for (int e = 0; e < EPV; ++e) s[e] = s[e] + w[e];
+                    }
+                }
+            }
+        }
+        #pragma unroll
+        for (int h = 0; h < EPV / 4; ++h) {
+            const f32x4 o = {a[4 * h] + s[4 * h], a[4 * h + 1] + s[4 * h + 1], a[4 * h + 2] + s[4 * h + 2],
+                             a[4 * h + 3] + s[4 * h + 3]};
+            st<kRsaNts>((f32x4*)acc + (EPV / 4) * i + h, o);
+        }
+    }
+}
+
+template <int KIND, bool ACCUM>
+__global__ __launch_bounds__(kBlock) void rsa_typed_scalar_kernel(
+    float* __restrict__ acc, PtrTable g, int p, size_t first, size_t count)
+{
+    const size_t stride = (size_t)gridDim.x * kBlock;
+    for (size_t x = first + (size_t)blockIdx.x * kBlock + threadIdx.x; x < count; x += stride) {
+        float partial = widen_one<KIND>(g.ptr[0], x);
+        for (int q = 1; q < p; ++q) partial = partial + widen_one<KIND>(g.ptr[q], x);
+        acc[x] = (ACCUM ? acc[x] : 0.0f) + partial;
+    }
+}
+
 // One element per lane: the tail of the vector kernels (elements [first, count))
 // and the whole range when some buffer is not 16-byte aligned.
 template <bool ACCUM>
@@ -1013,6 +1106,55 @@ int launch_avg_adam(float* master, float* exp_avg, float* exp_avg_sq, uint16_t* 
         if (int e = launch_status()) return e;
     }
     return 0;
+}
+
+namespace {
+template <int KIND, int P, bool ACCUM>
+void rsa_typed_launch(float* acc, const PtrTable& g, int p, size_t nvec, unsigned blocks, hipStream_t st)
+{
+    if constexpr (P > 0)
+        hipLaunchKernelGGL((rsa_typed_vec_kernel<KIND, P, ACCUM, SmallTable<P>>), dim3(blocks),
+                           dim3(kRsaBlock), 0, st, acc, small<P>(g), p, nvec);
+    else
+        hipLaunchKernelGGL((rsa_typed_vec_kernel<KIND, 0, ACCUM, PtrTable>), dim3(blocks), dim3(kRsaBlock),
+                           0, st, acc, g, p, nvec);
+}
+
+template <int KIND, bool ACCUM>
+int rsa_typed_all(float* acc, const PtrTable& g, size_t count, int p, bool vec16, hipStream_t st)
+{
+    constexpr size_t EPV = KIND == 1 ? 8 : 4;
+    const size_t nvec = vec16 ? count / EPV : 0;
+    unsigned blocks = 0;
+    if (nvec) {
+        if (int e = grid_for(nvec, kRsaBlock, MICS_RSA_BPC, &blocks)) return e;
+        switch (p) {
+            case 8: rsa_typed_launch<KIND, 8, ACCUM>(acc, g, p, nvec, blocks, st); break;
+            case 16: rsa_typed_launch<KIND, 16, ACCUM>(acc, g, p, nvec, blocks, st); break;
+            default: rsa_typed_launch<KIND, 0, ACCUM>(acc, g, p, nvec, blocks, st);
+        }
+        if (int e = launch_status()) return e;
+    }
+    const size_t first = nvec * EPV;
+    if (first < count) {
+        if (int e = grid_for(count - first, kBlock, kTailBpc, &blocks)) return e;
+        hipLaunchKernelGGL((rsa_typed_scalar_kernel<KIND, ACCUM>), dim3(blocks), dim3(kBlock), 0, st, acc, g,
+                           p, first, count);
+        if (int e = launch_status()) return e;
+    }
+    return 0;
+}
+}  // namespace
+
+int launch_reduce_scatter_accum_typed(float* acc, const PtrTable& g, size_t count, int p,
+                                      bool accumulate, int kind, bool vec16, void* stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    if (kind == 1)
+        return accumulate ? rsa_typed_all<1, true>(acc, g, count, p, vec16, st)
+                          : rsa_typed_all<1, false>(acc, g, count, p, vec16, st);
+    return accumulate ? rsa_typed_all<2, true>(acc, g, count, p, vec16, st)
+                      : rsa_typed_all<2, false>(acc, g, count, p, vec16, st);
 }
 
 }  // namespace mics

@@ -417,3 +417,48 @@ def test_fused_average_adam_equals_the_two_separate_calls_and_the_oracle(orc, ge
     assert all(x.guards_intact() for x in fused + copies) and (pb_f is None or pb_f.guards_intact())
     for c, h in zip(copies, copies_h):
         assert np.array_equal(c.numpy(), h), "an accumulator copy was modified"
+
+
+# ---- gradients stored as binary16 / binary32 ----------------------------------------------------------
+
+@pytest.mark.parametrize("dtype_name", ["f16", "f32"])
+@pytest.mark.parametrize("p,total,off,count,steps,skew", [
+    (8, 70000, 8, 69987, 2, 0), (16, 3 * 2048 * 8 + 40, 0, 3 * 2048 * 8 + 40, 3, 0),
+    (5, 30000, 16, 20001, 2, 0), (40, 20000, 0, 20000, 2, 0), (4, 30000, 3, 20000, 2, 0),
+    (8, 30000, 0, 30000, 2, 1), (1, 4100, 0, 4100, 1, 0),
+])
+def test_typed_reduce_scatter_accum_matches_oracle_bit_for_bit(orc, gen, dtype_name, p, total, off, count,
+                                                                steps, skew):
+    if dtype_name == "f32":
+        dtype, np_dt, code = mics.MICS_DTYPE_F32, np.float32, orc.DTYPE_F32
+        tab = gen.normal_table(1e-3, "f32")
+    else:
+        dtype, np_dt, code = mics.MICS_DTYPE_F16, np.uint16, orc.DTYPE_F16
+        # sigma = 3e-5: about half of the values are binary16 subnormals
+        tab = gen.normal_table(3e-5, "f32").astype(np.float16).view(np.uint16)
+    acc = Guarded(count, np.float32, skew=skew)
+    ref = np.full(count, np.nan, np.float32)
+    for t in range(steps):
+        host = [gen.fill_host(gen.stream_key(950, gen.ROLE_GRAD, 0, t, q), 0, total, tab) for q in range(p)]
+        dev = [Guarded(total, np_dt, skew=skew, fill=h) for h in host]
+        mics.mics_reduce_scatter_accum_typed(acc.t, [d.t for d in dev], off, count, t > 0, dtype)
+        torch.cuda.synchronize()
+        orc.reduce_scatter_accum_typed(ref, host, off, t > 0, code)
+        assert all(d.guards_intact() for d in dev)
+    assert np.array_equal(acc.numpy().view(np.uint32), ref.view(np.uint32))
+    assert acc.guards_intact()
+    assert np.abs(ref).max() > 0
+
+
+def test_typed_entry_point_with_bf16_is_the_plain_one(orc, gen):
+    p, n = 16, 40000
+    tab = gen.normal_table(1e-3, "bf16")
+    host = [gen.fill_host(gen.stream_key(951, gen.ROLE_GRAD, 0, 0, q), 0, n, tab) for q in range(p)]
+    dev = [upload(h) for h in host]
+    a = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    b = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    mics.mics_reduce_scatter_accum_typed(a, dev, 0, n, False, mics.MICS_DTYPE_BF16)
+    mics.mics_reduce_scatter_accum(b, dev, 0, n, False)
+    assert torch.equal(a, b)
+    with pytest.raises(mics.MicsError):
+        mics.mics_reduce_scatter_accum_typed(a, dev, 0, n, False, 7)
