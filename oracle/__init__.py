@@ -20,18 +20,21 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "mics_oracle.c")
 _LIB = os.path.join(_HERE, "libmics_oracle.so")
+# The mutation test (tests/test_oracle_mutants.py) points this at deliberately broken builds of
+# the oracle to show that the pins notice; nothing else sets it.
+_LIB_OVERRIDE = os.environ.get("MICS_ORACLE_LIB")
 
 CFLAGS = ["-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
           "-shared", "-fPIC", "-Wall", "-Wextra"]
 
 
-def build(force: bool = True) -> str:
+def build(force: bool = True, src: str = _SRC, out: str = _LIB) -> str:
     """Compile the oracle with gcc.  Returns the path of the shared object."""
-    if force or not os.path.exists(_LIB):
-        tmp = _LIB + f".tmp{os.getpid()}"
-        subprocess.run(["gcc", *CFLAGS, "-o", tmp, _SRC, "-lm"], check=True)
-        os.replace(tmp, _LIB)
-    return _LIB
+    if force or not os.path.exists(out):
+        tmp = out + f".tmp{os.getpid()}"
+        subprocess.run(["gcc", *CFLAGS, f"-I{_HERE}", "-o", tmp, src, "-lm"], check=True)
+        os.replace(tmp, out)
+    return out
 
 
 _lib = None
@@ -40,9 +43,12 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        if not os.path.exists(_LIB):
-            build()
-        lib = ctypes.CDLL(_LIB)
+        if _LIB_OVERRIDE:
+            lib = ctypes.CDLL(_LIB_OVERRIDE)
+        else:
+            if not os.path.exists(_LIB):
+                build()
+            lib = ctypes.CDLL(_LIB)
         vp, sz, i32, f32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_float
         lib.orc_set_threads.argtypes = [i32]
         lib.orc_set_threads.restype = i32

@@ -15,7 +15,8 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def orc():
     import oracle
-    oracle.build(force=False)
+    if not oracle._LIB_OVERRIDE:
+        oracle.build(force=False)
     return oracle
 
 

@@ -462,3 +462,54 @@ def test_typed_entry_point_with_bf16_is_the_plain_one(orc, gen):
     assert torch.equal(a, b)
     with pytest.raises(mics.MicsError):
         mics.mics_reduce_scatter_accum_typed(a, dev, 0, n, False, 7)
+
+
+# ---- stream order and graph capture ----------------------------------------------------------------------
+
+def test_calls_are_stream_ordered_and_survive_hip_graph_capture(orc, gen):
+    """The library allocates nothing, never synchronises and enqueues no memsets, so a whole
+    step can be captured into a HIP graph on a side stream and replayed; every replay must
+    reproduce the eager result."""
+    p, r, s, S = 8, 2, 3, 20000
+    hp = dict(HP)
+    scale = float(np.float32(1.0 / (r * p * s)))
+    tab = gen.normal_table(1e-3, "bf16")
+    grads = [[upload(gen.fill_host(gen.stream_key(970, gen.ROLE_GRAD, 0, t, q), 0, S, tab)) for q in range(p)]
+             for t in range(s)]
+    other = upload(gen.fill_host(gen.stream_key(970, gen.ROLE_ACC, 1), 0, S, gen.normal_table(5e-3, "f32")))
+    w0 = upload(gen.fill_host(gen.stream_key(970, gen.ROLE_MASTER), 0, S, gen.normal_table(0.02, "f32")))
+    acc = torch.empty(S, dtype=torch.float32, device="cuda:0")
+    avg = torch.empty_like(acc)
+    w, m, v = torch.empty_like(acc), torch.empty_like(acc), torch.empty_like(acc)
+    pb = torch.empty(S, dtype=torch.int16, device="cuda:0")
+
+    def one_step():
+        # state is reset by copies on the same stream, so every run starts alike
+        w.copy_(w0); m.fill_(0.0); v.fill_(0.0)
+        for t in range(s):
+            mics.mics_reduce_scatter_accum(acc, grads[t], 0, S, t > 0)
+        mics.mics_replica_average(avg, [acc, other], S, scale)
+        mics.mics_adam_shard(w, m, v, pb, avg, S, step=1, **hp)
+
+    one_step()
+    torch.cuda.synchronize()
+    eager = [x.clone() for x in (acc, avg, w, m, v, pb)]
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        one_step()                                   # warm-up on the capture stream
+        with torch.cuda.graph(graph, stream=side):
+            one_step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for replay in range(3):
+        for x in (acc, avg, w, m, v):                # eager work between the replays
+            x.fill_(float(replay + 7))
+        pb.fill_(replay)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((acc, avg, w, m, v, pb), eager):
+            assert torch.equal(got, want), f"replay {replay} differs from the eager result"
