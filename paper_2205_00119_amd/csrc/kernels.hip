@@ -18,6 +18,7 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <type_traits>
 
 #include "internal.h"
 
@@ -57,9 +58,6 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #ifndef MICS_RSA_NTL
 #define MICS_RSA_NTL 1
 #endif
-#ifndef MICS_RSA_NTS
-#define MICS_RSA_NTS 0
-#endif
 #ifndef MICS_AVG_BLOCK
 #define MICS_AVG_BLOCK 512
 #endif
@@ -68,9 +66,6 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #endif
 #ifndef MICS_AVG_NTL
 #define MICS_AVG_NTL 1
-#endif
-#ifndef MICS_AVG_NTS
-#define MICS_AVG_NTS 0
 #endif
 #ifndef MICS_ADAM_BLOCK
 #define MICS_ADAM_BLOCK 256
@@ -91,8 +86,8 @@ constexpr int kRsaBlock = MICS_RSA_BLOCK;
 constexpr int kAvgBlock = MICS_AVG_BLOCK;
 constexpr int kAdamBlock = MICS_ADAM_BLOCK;
 constexpr bool kReorderNtl = MICS_REORDER_NTL, kReorderNts = MICS_REORDER_NTS;
-constexpr bool kRsaNtl = MICS_RSA_NTL, kRsaNts = MICS_RSA_NTS;
-constexpr bool kAvgNtl = MICS_AVG_NTL, kAvgNts = MICS_AVG_NTS;
+constexpr bool kRsaNtl = MICS_RSA_NTL;   // gradient loads; the accumulator's hint is chosen per launch
+constexpr bool kAvgNtl = MICS_AVG_NTL;   // input loads; the output's hint is chosen per launch
 constexpr bool kAdamNtl = MICS_ADAM_NTL, kAdamNts = MICS_ADAM_NTS;
 
 // Compile-time sized pointer table for the unrolled kernels (keeps the
@@ -395,39 +390,44 @@ __device__ __forceinline__ void rsa_partial8(float (&s)[8], const Tab& g, int p,
 }
 
 // acc8 (16-byte aligned, 8 floats) = (ACCUM ? acc8 : +0) + partial sum at `elem`.
-template <int P, bool ACCUM, typename Tab>
+// SA ("stream the accumulator"): non-temporal accumulator loads and stores.  An accumulator
+// that fits the 256 MB Infinity Cache is best left cacheable -- its stores are absorbed there
+// and the next micro-step finds it again (plain/plain 6.3 TB/s, NT/NT 6.1 at S = 50 M) -- while
+// a larger one is best streamed past the caches (NT/NT 5.8 TB/s, plain/plain 5.4, and the
+// mixed NT-load/plain-store 5.1 at S = 200 M); the launcher picks by size.
+template <int P, bool ACCUM, bool SA, typename Tab>
 __device__ __forceinline__ void rsa_update8(float* __restrict__ acc8, const Tab& g, int p, size_t elem)
 {
     f32x4 a0 = {0.0f, 0.0f, 0.0f, 0.0f}, a1 = a0;
     if (ACCUM) {   // issued before the gradient loads are consumed
-        a0 = ld<kRsaNtl>((const f32x4*)acc8);
-        a1 = ld<kRsaNtl>((const f32x4*)acc8 + 1);
+        a0 = ld<SA>((const f32x4*)acc8);
+        a1 = ld<SA>((const f32x4*)acc8 + 1);
     }
     float s[8];
     rsa_partial8<P>(s, g, p, elem);
     f32x4 o0 = {a0.x + s[0], a0.y + s[1], a0.z + s[2], a0.w + s[3]};
     f32x4 o1 = {a1.x + s[4], a1.y + s[5], a1.z + s[6], a1.w + s[7]};
-    st<kRsaNts>((f32x4*)acc8, o0);
-    st<kRsaNts>((f32x4*)acc8 + 1, o1);
+    st<SA>((f32x4*)acc8, o0);
+    st<SA>((f32x4*)acc8 + 1, o1);
 }
 
-template <int P, bool ACCUM>
+template <int P, bool ACCUM, bool SA>
 __global__ __launch_bounds__(kRsaBlock) void rsa_vec_kernel(
     float* __restrict__ acc, SmallTable<P> g, size_t nvec)
 {
     const size_t stride = (size_t)gridDim.x * kRsaBlock;
     for (size_t i = (size_t)blockIdx.x * kRsaBlock + threadIdx.x; i < nvec; i += stride)
-        rsa_update8<P, ACCUM>(acc + 8 * i, g, P, 8 * i);
+        rsa_update8<P, ACCUM, SA>(acc + 8 * i, g, P, 8 * i);
 }
 
 // Any p.
-template <bool ACCUM>
+template <bool ACCUM, bool SA>
 __global__ __launch_bounds__(kRsaBlock) void rsa_vec_anyp_kernel(
     float* __restrict__ acc, PtrTable g, int p, size_t nvec)
 {
     const size_t stride = (size_t)gridDim.x * kRsaBlock;
     for (size_t i = (size_t)blockIdx.x * kRsaBlock + threadIdx.x; i < nvec; i += stride)
-        rsa_update8<0, ACCUM>(acc + 8 * i, g, p, 8 * i);
+        rsa_update8<0, ACCUM, SA>(acc + 8 * i, g, p, 8 * i);
 }
 
 // Coalesced form (many separately sharded tensors in one launch): workgroup x works on tile
@@ -442,7 +442,7 @@ struct ReduceSegTable {
     ReduceSeg seg[kMaxSeg];
 };
 
-template <int P, bool ACCUM, typename Tab>
+template <int P, bool ACCUM, bool SA, typename Tab>
 __global__ __launch_bounds__(kRsaBlock) void rsa_seg_kernel(
     float* __restrict__ acc, Tab g, int p, ReduceSegTable tab)
 {
@@ -452,7 +452,7 @@ __global__ __launch_bounds__(kRsaBlock) void rsa_seg_kernel(
     const size_t e0 = ((size_t)(x - tab.tile_begin[t]) * kRsaBlock + threadIdx.x) * 8;
     if (e0 >= count) return;
     if (e0 + 8 <= count) {
-        rsa_update8<P, ACCUM>(acc + dst + e0, g, p, src + e0);
+        rsa_update8<P, ACCUM, SA>(acc + dst + e0, g, p, src + e0);
     } else {
         for (size_t e = e0; e < count; ++e) {
             float partial = bf16_one(((const uint16_t*)g.ptr[0])[src + e]);
@@ -489,7 +489,7 @@ __device__ __forceinline__ float widen_one(const void* buf, size_t x)
     else return ((const float*)buf)[x];
 }
 
-template <int KIND, int P, bool ACCUM, typename Tab>
+template <int KIND, int P, bool ACCUM, bool SA, typename Tab>
 __global__ __launch_bounds__(kRsaBlock) void rsa_typed_vec_kernel(
     float* __restrict__ acc, Tab g, int p, size_t nvec)
 {
@@ -500,7 +500,7 @@ __global__ __launch_bounds__(kRsaBlock) void rsa_typed_vec_kernel(
         if (ACCUM) {
             #pragma unroll
             for (int h = 0; h < EPV / 4; ++h) {
-                const f32x4 t = ld<kRsaNtl>((const f32x4*)acc + (EPV / 4) * i + h);
+                const f32x4 t = ld<SA>((const f32x4*)acc + (EPV / 4) * i + h);
                 a[4 * h] = t.x; a[4 * h + 1] = t.y; a[4 * h + 2] = t.z; a[4 * h + 3] = t.w;
             }
         }
@@ -538,7 +538,7 @@ __global__ __launch_bounds__(kRsaBlock) void rsa_typed_vec_kernel(
         for (int h = 0; h < EPV / 4; ++h) {
             const f32x4 o = {a[4 * h] + s[4 * h], a[4 * h + 1] + s[4 * h + 1], a[4 * h + 2] + s[4 * h + 2],
                              a[4 * h + 3] + s[4 * h + 3]};
-            st<kRsaNts>((f32x4*)acc + (EPV / 4) * i + h, o);
+            st<SA>((f32x4*)acc + (EPV / 4) * i + h, o);
         }
     }
 }
@@ -573,7 +573,9 @@ __global__ __launch_bounds__(kBlock) void rsa_scalar_kernel(
 // before it writes them, and no other lane touches them.
 // ---------------------------------------------------------------------------
 
-template <int R>
+// SO ("stream the output"): non-temporal stores for results too large for the Infinity Cache,
+// as for the accumulator of the reduce kernels.
+template <int R, bool SO>
 __global__ __launch_bounds__(kAvgBlock) void avg_vec_kernel(
     float* out, SmallTable<R> a, float scale, size_t nvec)
 {
@@ -585,10 +587,11 @@ __global__ __launch_bounds__(kAvgBlock) void avg_vec_kernel(
         f32x4 sv = v[0];
         #pragma unroll
         for (int c = 1; c < R; ++c) sv = sv + v[c];
-        st<kAvgNts>((f32x4*)out + i, sv * scale);
+        st<SO>((f32x4*)out + i, sv * scale);
     }
 }
 
+template <bool SO>
 __global__ __launch_bounds__(kAvgBlock) void avg_vec_anyr_kernel(
     float* out, PtrTable a, int r, float scale, size_t nvec)
 {
@@ -605,7 +608,7 @@ __global__ __launch_bounds__(kAvgBlock) void avg_vec_anyr_kernel(
             for (int b = 0; b < B; ++b)
                 if (c0 + b < r) sum = sum + v[b];
         }
-        st<kAvgNts>((f32x4*)out + i, sum * scale);
+        st<SO>((f32x4*)out + i, sum * scale);
     }
 }
 
@@ -811,6 +814,18 @@ inline int launch_status()
     return e == hipSuccess ? 0 : (int)e;
 }
 
+// Accumulators up to this size are left cacheable, larger ones are streamed (see rsa_update8).
+constexpr size_t kAccCacheableBytes = 224u << 20;
+inline bool stream_acc(size_t elements) { return elements * 4 > kAccCacheableBytes; }
+
+// Calls f(std::bool_constant<a>, std::bool_constant<b>) for two runtime flags.
+template <typename F>
+void dispatch2(bool a, bool b, F&& f)
+{
+    if (a) { if (b) f(std::true_type{}, std::true_type{}); else f(std::true_type{}, std::false_type{}); }
+    else   { if (b) f(std::false_type{}, std::true_type{}); else f(std::false_type{}, std::false_type{}); }
+}
+
 template <int N>
 SmallTable<N> small(const PtrTable& t)
 {
@@ -823,20 +838,20 @@ template <int P>
 void rsa_launch_fixed(float* acc, const PtrTable& g, size_t nvec, bool accumulate, unsigned blocks,
                       hipStream_t st)
 {
-    if (accumulate)
-        hipLaunchKernelGGL((rsa_vec_kernel<P, true>), dim3(blocks), dim3(kRsaBlock), 0, st, acc,
+    dispatch2(accumulate, stream_acc(nvec * 8), [&](auto A, auto SA) {
+        hipLaunchKernelGGL((rsa_vec_kernel<P, A.value, SA.value>), dim3(blocks), dim3(kRsaBlock), 0, st, acc,
                            small<P>(g), nvec);
-    else
-        hipLaunchKernelGGL((rsa_vec_kernel<P, false>), dim3(blocks), dim3(kRsaBlock), 0, st, acc,
-                           small<P>(g), nvec);
+    });
 }
 
 template <int R>
 void avg_launch_fixed(float* out, const PtrTable& a, float scale, size_t nvec, unsigned blocks,
                       hipStream_t st)
 {
-    hipLaunchKernelGGL((avg_vec_kernel<R>), dim3(blocks), dim3(kAvgBlock), 0, st, out, small<R>(a),
-                       scale, nvec);
+    dispatch2(stream_acc(nvec * 4), false, [&](auto SO, auto) {
+        hipLaunchKernelGGL((avg_vec_kernel<R, SO.value>), dim3(blocks), dim3(kAvgBlock), 0, st, out,
+                           small<R>(a), scale, nvec);
+    });
 }
 
 }  // namespace
@@ -883,12 +898,10 @@ int launch_reduce_scatter_accum(float* acc, const PtrTable& g, size_t count, int
             case 16: rsa_launch_fixed<16>(acc, g, nvec, accumulate, blocks, st); break;
             case 32: rsa_launch_fixed<32>(acc, g, nvec, accumulate, blocks, st); break;
             default:
-                if (accumulate)
-                    hipLaunchKernelGGL(rsa_vec_anyp_kernel<true>, dim3(blocks), dim3(kRsaBlock),
-                                       0, st, acc, g, p, nvec);
-                else
-                    hipLaunchKernelGGL(rsa_vec_anyp_kernel<false>, dim3(blocks), dim3(kRsaBlock),
-                                       0, st, acc, g, p, nvec);
+                dispatch2(accumulate, stream_acc(count), [&](auto A, auto SA) {
+                    hipLaunchKernelGGL((rsa_vec_anyp_kernel<A.value, SA.value>), dim3(blocks),
+                                       dim3(kRsaBlock), 0, st, acc, g, p, nvec);
+                });
         }
         if (int e = launch_status()) return e;
     }
@@ -920,8 +933,10 @@ int launch_replica_average(float* out, const PtrTable& a, size_t count, int r, f
             case 4: avg_launch_fixed<4>(out, a, scale, nvec, blocks, st); break;
             case 8: avg_launch_fixed<8>(out, a, scale, nvec, blocks, st); break;
             default:
-                hipLaunchKernelGGL(avg_vec_anyr_kernel, dim3(blocks), dim3(kAvgBlock), 0, st, out,
-                                   a, r, scale, nvec);
+                dispatch2(stream_acc(count), false, [&](auto SO, auto) {
+                    hipLaunchKernelGGL(avg_vec_anyr_kernel<SO.value>, dim3(blocks), dim3(kAvgBlock), 0, st,
+                                       out, a, r, scale, nvec);
+                });
         }
         if (int e = launch_status()) return e;
     }
@@ -996,23 +1011,16 @@ int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs
 namespace {
 template <int P>
 void rsa_seg_launch(float* acc, const PtrTable& g, int p, const ReduceSegTable& tab, unsigned tiles,
-                    bool accumulate, hipStream_t st)
+                    bool accumulate, bool sa, hipStream_t st)
 {
-    if constexpr (P > 0) {
-        if (accumulate)
-            hipLaunchKernelGGL((rsa_seg_kernel<P, true, SmallTable<P>>), dim3(tiles), dim3(kRsaBlock), 0,
-                               st, acc, small<P>(g), p, tab);
+    dispatch2(accumulate, sa, [&](auto A, auto SA) {
+        if constexpr (P > 0)
+            hipLaunchKernelGGL((rsa_seg_kernel<P, A.value, SA.value, SmallTable<P>>), dim3(tiles),
+                               dim3(kRsaBlock), 0, st, acc, small<P>(g), p, tab);
         else
-            hipLaunchKernelGGL((rsa_seg_kernel<P, false, SmallTable<P>>), dim3(tiles), dim3(kRsaBlock), 0,
-                               st, acc, small<P>(g), p, tab);
-    } else {
-        if (accumulate)
-            hipLaunchKernelGGL((rsa_seg_kernel<0, true, PtrTable>), dim3(tiles), dim3(kRsaBlock), 0, st,
-                               acc, g, p, tab);
-        else
-            hipLaunchKernelGGL((rsa_seg_kernel<0, false, PtrTable>), dim3(tiles), dim3(kRsaBlock), 0, st,
-                               acc, g, p, tab);
-    }
+            hipLaunchKernelGGL((rsa_seg_kernel<0, A.value, SA.value, PtrTable>), dim3(tiles), dim3(kRsaBlock),
+                               0, st, acc, g, p, tab);
+    });
 }
 }  // namespace
 
@@ -1024,9 +1032,10 @@ int launch_reduce_coalesced(float* acc, const PtrTable& g, const Segment* segs, 
     for (int first = 0; first < n; first += kMaxSeg) {
         ReduceSegTable tab;
         tab.n = n - first < kMaxSeg ? n - first : kMaxSeg;
-        size_t tiles = 0;
+        size_t tiles = 0, elements = 0;
         for (int t = 0; t < tab.n; ++t) {
             const Segment& sg = segs[first + t];
+            elements += sg.numel;
             tab.tile_begin[t] = (unsigned)tiles;
             tab.seg[t].count = sg.numel;
             tab.seg[t].src_off = sg.src_offset;
@@ -1037,13 +1046,13 @@ int launch_reduce_coalesced(float* acc, const PtrTable& g, const Segment* segs, 
         for (int t = tab.n; t <= kMaxSeg; ++t) tab.tile_begin[t] = 0xFFFFFFFFu;
         if (tiles == 0) continue;
         switch (p) {
-            case 1: rsa_seg_launch<1>(acc, g, p, tab, (unsigned)tiles, accumulate, st); break;
-            case 2: rsa_seg_launch<2>(acc, g, p, tab, (unsigned)tiles, accumulate, st); break;
-            case 4: rsa_seg_launch<4>(acc, g, p, tab, (unsigned)tiles, accumulate, st); break;
-            case 8: rsa_seg_launch<8>(acc, g, p, tab, (unsigned)tiles, accumulate, st); break;
-            case 16: rsa_seg_launch<16>(acc, g, p, tab, (unsigned)tiles, accumulate, st); break;
-            case 32: rsa_seg_launch<32>(acc, g, p, tab, (unsigned)tiles, accumulate, st); break;
-            default: rsa_seg_launch<0>(acc, g, p, tab, (unsigned)tiles, accumulate, st);
+            case 1: rsa_seg_launch<1>(acc, g, p, tab, (unsigned)tiles, accumulate, stream_acc(elements), st); break;
+            case 2: rsa_seg_launch<2>(acc, g, p, tab, (unsigned)tiles, accumulate, stream_acc(elements), st); break;
+            case 4: rsa_seg_launch<4>(acc, g, p, tab, (unsigned)tiles, accumulate, stream_acc(elements), st); break;
+            case 8: rsa_seg_launch<8>(acc, g, p, tab, (unsigned)tiles, accumulate, stream_acc(elements), st); break;
+            case 16: rsa_seg_launch<16>(acc, g, p, tab, (unsigned)tiles, accumulate, stream_acc(elements), st); break;
+            case 32: rsa_seg_launch<32>(acc, g, p, tab, (unsigned)tiles, accumulate, stream_acc(elements), st); break;
+            default: rsa_seg_launch<0>(acc, g, p, tab, (unsigned)tiles, accumulate, stream_acc(elements), st);
         }
         if (int e = launch_status()) return e;
     }
@@ -1110,14 +1119,17 @@ int launch_avg_adam(float* master, float* exp_avg, float* exp_avg_sq, uint16_t* 
 
 namespace {
 template <int KIND, int P, bool ACCUM>
-void rsa_typed_launch(float* acc, const PtrTable& g, int p, size_t nvec, unsigned blocks, hipStream_t st)
+void rsa_typed_launch(float* acc, const PtrTable& g, int p, size_t nvec, bool sa, unsigned blocks,
+                      hipStream_t st)
 {
-    if constexpr (P > 0)
-        hipLaunchKernelGGL((rsa_typed_vec_kernel<KIND, P, ACCUM, SmallTable<P>>), dim3(blocks),
-                           dim3(kRsaBlock), 0, st, acc, small<P>(g), p, nvec);
-    else
-        hipLaunchKernelGGL((rsa_typed_vec_kernel<KIND, 0, ACCUM, PtrTable>), dim3(blocks), dim3(kRsaBlock),
-                           0, st, acc, g, p, nvec);
+    dispatch2(sa, false, [&](auto SA, auto) {
+        if constexpr (P > 0)
+            hipLaunchKernelGGL((rsa_typed_vec_kernel<KIND, P, ACCUM, SA.value, SmallTable<P>>), dim3(blocks),
+                               dim3(kRsaBlock), 0, st, acc, small<P>(g), p, nvec);
+        else
+            hipLaunchKernelGGL((rsa_typed_vec_kernel<KIND, 0, ACCUM, SA.value, PtrTable>), dim3(blocks),
+                               dim3(kRsaBlock), 0, st, acc, g, p, nvec);
+    });
 }
 
 template <int KIND, bool ACCUM>
@@ -1129,9 +1141,9 @@ int rsa_typed_all(float* acc, const PtrTable& g, size_t count, int p, bool vec16
     if (nvec) {
         if (int e = grid_for(nvec, kRsaBlock, MICS_RSA_BPC, &blocks)) return e;
         switch (p) {
-            case 8: rsa_typed_launch<KIND, 8, ACCUM>(acc, g, p, nvec, blocks, st); break;
-            case 16: rsa_typed_launch<KIND, 16, ACCUM>(acc, g, p, nvec, blocks, st); break;
-            default: rsa_typed_launch<KIND, 0, ACCUM>(acc, g, p, nvec, blocks, st);
+            case 8: rsa_typed_launch<KIND, 8, ACCUM>(acc, g, p, nvec, stream_acc(count), blocks, st); break;
+            case 16: rsa_typed_launch<KIND, 16, ACCUM>(acc, g, p, nvec, stream_acc(count), blocks, st); break;
+            default: rsa_typed_launch<KIND, 0, ACCUM>(acc, g, p, nvec, stream_acc(count), blocks, st);
         }
         if (int e = launch_status()) return e;
     }
