@@ -304,9 +304,9 @@ def main():
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
 # each scaled by what the same counter reads for a plain copy of known size (factors 1.9999 and
-# 0.9986), averaged over a step's 11 accumulating + 1 overwriting launches
+# 0.9983), averaged over a step's 11 accumulating + 1 overwriting launches
 # (profiles/all_kernels_h8192_rank_view.md).  None = not measured for that workload.
-MEASURED_TRAFFIC = {("h8192", "rank"): (11 * 2014869161 + 1811902398) // 12}
+MEASURED_TRAFFIC = {("h8192", "rank"): (11 * 2013200701 + 1811857686) // 12}
 
 
 def cpu_baseline(cfg, args):
