@@ -513,3 +513,65 @@ def test_calls_are_stream_ordered_and_survive_hip_graph_capture(orc, gen):
         torch.cuda.synchronize()
         for got, want in zip((acc, avg, w, m, v, pb), eager):
             assert torch.equal(got, want), f"replay {replay} differs from the eager result"
+
+
+# ---- capped grids: every kernel's stride loop ---------------------------------------------------------
+
+def test_capped_grids_give_the_same_results(orc, gen):
+    """With at most one workgroup per compute unit every lane makes several passes; the results
+    must not change (the default grids cover the data in one pass, so this is the only place
+    the stride loops are exercised)."""
+    p, k, r, S = 16, 8, 8, 256 * 1024 * 3 + 40      # ~3 passes of 256 CUs x 1024 lanes... and a tail
+    n = p * S - 9
+    tab = gen.normal_table(1e-3, "bf16")
+    try:
+        mics.mics_set_blocks_per_cu(1)
+        # reorder
+        shards = [tagged(gen, 3000 + g, S, np.uint16) for g in range(p)]
+        T = [orc.stage1_gather(shards, k, l) for l in range(k)]
+        dst = Guarded(p * S, np.uint16)
+        mics.mics_hier_gather_reorder(dst.t, [upload(t) for t in T], n, S, p, k, 2)
+        torch.cuda.synchronize()
+        assert np.array_equal(dst.numpy()[:n], orc.concat_shards(shards, n)) and dst.guards_intact()
+        del shards, T
+        # reduce-scatter-accumulate, two micro-steps (bf16 and fp32 gradients)
+        acc = Guarded(S, np.float32)
+        ref = np.empty(S, np.float32)
+        for t in range(2):
+            host = [gen.fill_host(gen.stream_key(990, gen.ROLE_GRAD, 0, t, q), 0, S, tab) for q in range(p)]
+            mics.mics_reduce_scatter_accum(acc.t, [upload(h) for h in host], 0, S, t > 0)
+            orc.reduce_scatter_accum(ref, host, 0, t > 0)
+        torch.cuda.synchronize()
+        assert np.array_equal(acc.numpy().view(np.uint32), ref.view(np.uint32)) and acc.guards_intact()
+        f32 = [orc.bf16_widen(h) for h in host[:5]]
+        acc32 = Guarded(S, np.float32)
+        mics.mics_reduce_scatter_accum_typed(acc32.t, [upload(h) for h in f32], 0, S, False, mics.MICS_DTYPE_F32)
+        ref32 = orc.reduce_scatter_accum_typed(np.empty(S, np.float32), f32, 0, False, orc.DTYPE_F32)
+        torch.cuda.synchronize()
+        assert np.array_equal(acc32.numpy().view(np.uint32), ref32.view(np.uint32))
+        # replica average, Adam, and the fused form
+        atab = gen.normal_table(1e-2, "f32")
+        copies = [gen.fill_host(gen.stream_key(990, gen.ROLE_ACC, c), 0, S, atab) for c in range(r)]
+        copies_d = [upload(c) for c in copies]
+        scale = float(np.float32(1.0 / 1536))
+        avg = Guarded(S, np.float32)
+        mics.mics_replica_average(avg.t, copies_d, S, scale)
+        avg_ref = orc.replica_average(copies, scale)
+        torch.cuda.synchronize()
+        assert np.array_equal(avg.numpy().view(np.uint32), avg_ref.view(np.uint32)) and avg.guards_intact()
+        w0 = gen.fill_host(gen.stream_key(990, gen.ROLE_MASTER), 0, S, gen.normal_table(0.02, "f32"))
+        wr, mr, vr = w0.copy(), np.zeros(S, np.float32), np.zeros(S, np.float32)
+        pbr = orc.adam_shard(wr, mr, vr, avg_ref, step=3, f32=True, **HP)
+        for fused in (False, True):
+            w, m, v = upload(w0.copy()), upload(np.zeros(S, np.float32)), upload(np.zeros(S, np.float32))
+            pb = Guarded(S, np.uint16)
+            if fused:
+                mics.mics_replica_average_adam_shard(w, m, v, pb.t, copies_d, S, scale, step=3, **HP)
+            else:
+                mics.mics_adam_shard(w, m, v, pb.t, avg.t, S, step=3, **HP)
+            torch.cuda.synchronize()
+            assert np.array_equal(w.cpu().numpy().view(np.uint32), wr.view(np.uint32))
+            assert np.array_equal(v.cpu().numpy().view(np.uint32), vr.view(np.uint32))
+            assert np.array_equal(pb.numpy(), pbr) and pb.guards_intact()
+    finally:
+        mics.mics_set_blocks_per_cu(0)
