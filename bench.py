@@ -116,27 +116,32 @@ def main():
 
         # a2: per micro-step, p gradient buffers covering the elements this call owns
         n_sets = 1 if group else s
+        # Each rank buffer is its own 16-byte aligned allocation in a real run, and the rank reads
+        # it from element offset g*S on: rows are padded so that every view below starts at the
+        # same position inside a 16-byte line as that offset would (0 unless S is odd).
+        lead = offset % 8
+        row = -(-(lead + count) // 8) * 8
         if args.grad_dtype == "bf16":
-            grads = torch.empty((n_sets, p, count), dtype=torch.int16, device=dev)
+            grads = torch.empty((n_sets, p, row), dtype=torch.int16, device=dev)
             g_tab, g_out, g_bytes = tab_g, tab_go, 2
         elif args.grad_dtype == "f16":
-            grads = torch.empty((n_sets, p, count), dtype=torch.int16, device=dev)
+            grads = torch.empty((n_sets, p, row), dtype=torch.int16, device=dev)
             as_f16 = lambda sig: torch.from_numpy(
                 synth.normal_table(sig, "f32").astype(np.float16).view(np.int16)).to(dev)
             g_tab = as_f16(cfg.sigma_grad * 1024)          # loss-scaled by 2^10
             g_out = as_f16(cfg.sigma_grad * 1024 * cfg.outlier_scale) if cfg.outlier_frac else None
             g_bytes = 2
         else:
-            grads = torch.empty((n_sets, p, count), dtype=torch.float32, device=dev)
+            grads = torch.empty((n_sets, p, row), dtype=torch.float32, device=dev)
             g_tab = torch.from_numpy(synth.normal_table(cfg.sigma_grad, "f32")).to(dev)
             g_out = (torch.from_numpy(synth.normal_table(cfg.sigma_grad * cfg.outlier_scale, "f32")).to(dev)
                      if cfg.outlier_frac else None)
             g_bytes = 4
         for t in range(n_sets):
             for q in range(p):
-                fill(grads[t, q], synth.stream_key(cfg.seed, synth.ROLE_GRAD, 0, t, q), offset, g_tab, g_bytes,
-                     g_out, cfg.outlier_frac)
-        grad_tables = [[grads[t % n_sets, q] for q in range(p)] for t in range(s)]
+                fill(grads[t, q, lead:lead + count], synth.stream_key(cfg.seed, synth.ROLE_GRAD, 0, t, q),
+                     offset, g_tab, g_bytes, g_out, cfg.outlier_frac)
+        grad_tables = [[grads[t % n_sets, q, lead:lead + count] for q in range(p)] for t in range(s)]
     else:
         if group or cfg.name == "tiny" or cfg.align != 8:
             print("--coalesced needs a transformer-layer configuration in rank view", file=sys.stderr)

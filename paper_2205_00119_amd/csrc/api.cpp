@@ -30,6 +30,16 @@ inline bool overlaps(const void* a, size_t an, const void* b, size_t bn)
     return an && bn && addr(a) < addr(b) + bn && addr(b) < addr(a) + an;
 }
 
+// Running common offset of gradient pointers inside their 16-byte lines: start with -2 (nothing
+// seen; -1 if the accumulator itself is not 16-byte aligned), feed every pointer; the result is
+// the shared offset 0..14, or -1 if the pointers disagree.
+int common_phase(int so_far, const void* ptr)
+{
+    const int ph = (int)(addr(ptr) & 15);
+    if (so_far == -2) return ph;
+    return so_far == ph ? so_far : -1;
+}
+
 int hip_fail(const char* what, int err)
 {
     return fail(MICS_ERR_HIP, "%s: HIP error %d (%s)", what, err, mics::hip_error_text(err));
@@ -135,6 +145,7 @@ int mics_reduce_scatter_accum_typed(float* acc, const void* const* grads, size_t
 
     mics::PtrTable tab{};
     bool vec16 = aligned(acc, 16);
+    int phase = aligned(acc, 16) ? -2 : -1;      // -2: not seen yet, -1: no common phase
     for (int q = 0; q < p; ++q) {
         const void* g = grads[q];
         if (!g) return fail(MICS_ERR_INVALID_ARG, "%s: grads_bf16[%d] is NULL", fn, q);
@@ -144,10 +155,11 @@ int mics_reduce_scatter_accum_typed(float* acc, const void* const* grads, size_t
         if (overlaps(acc, count * 4, first, count * gb))
             return fail(MICS_ERR_INVALID_ARG, "%s: acc overlaps grads_bf16[%d]", fn, q);
         vec16 = vec16 && aligned(first, 16);
+        phase = common_phase(phase, first);
         tab.ptr[q] = first;
     }
     int err = grad_dtype == MICS_DTYPE_BF16
-                  ? mics::launch_reduce_scatter_accum(acc, tab, count, p, accumulate != 0, vec16, stream)
+                  ? mics::launch_reduce_scatter_accum(acc, tab, count, p, accumulate != 0, phase, stream)
                   : mics::launch_reduce_scatter_accum_typed(acc, tab, count, p, accumulate != 0,
                                                             grad_dtype, vec16, stream);
     return err ? hip_fail(fn, err) : MICS_OK;
@@ -368,9 +380,13 @@ int mics_reduce_scatter_accum_coalesced(float* acc, const uint16_t* const* grads
                 ++nb;
             } else {
                 mics::PtrTable one{};
-                for (int q = 0; q < p; ++q) one.ptr[q] = (const uint16_t*)tab.ptr[q] + sg.src_offset;
+                int phase = aligned(acc + sg.dst_offset, 16) ? -2 : -1;
+                for (int q = 0; q < p; ++q) {
+                    one.ptr[q] = (const uint16_t*)tab.ptr[q] + sg.src_offset;
+                    phase = common_phase(phase, one.ptr[q]);
+                }
                 int err = mics::launch_reduce_scatter_accum(acc + sg.dst_offset, one, sg.numel, p,
-                                                            accumulate != 0, false, stream);
+                                                            accumulate != 0, phase, stream);
                 if (err) return hip_fail(fn, err);
             }
         }

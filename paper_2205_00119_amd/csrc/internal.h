@@ -23,9 +23,11 @@ struct PtrTable {
 int launch_reorder(void* dst, const PtrTable& src, size_t n_valid_bytes,
                    size_t shard_bytes, int p, int k, bool vec16, void* stream);
 
-// grads.ptr[q] already points at element elem_offset of rank q's buffer.
+// grads.ptr[q] already points at element elem_offset of rank q's buffer.  grad_phase: 0 = the
+// accumulator and every gradient pointer are 16-byte aligned; 2..14 = the accumulator is
+// aligned and every gradient pointer sits that many bytes into a 16-byte line; -1 = neither.
 int launch_reduce_scatter_accum(float* acc, const PtrTable& grads, size_t count,
-                                int p, bool accumulate, bool vec16, void* stream);
+                                int p, bool accumulate, int grad_phase, void* stream);
 
 int launch_replica_average(float* out, const PtrTable& copies, size_t count,
                            int r, float scale, bool vec16, void* stream);

@@ -430,6 +430,75 @@ __global__ __launch_bounds__(kRsaBlock) void rsa_vec_anyp_kernel(
         rsa_update8<0, ACCUM, SA>(acc + 8 * i, g, p, 8 * i);
 }
 
+// Rank buffers that all start at the same non-zero offset `phase` (even, 2..14 bytes) inside
+// their 16-byte lines -- what an odd shard size gives: rank g's slice of every buffer starts
+// at g*S elements -- while the accumulator is aligned.  A lane rebuilds its 8 elements of each
+// buffer from the two aligned vectors that hold them (funnel shift by the uniform phase); the
+// second load of a lane is the first load of its neighbour, so memory traffic does not grow.
+// g.ptr[q] is the buffer address rounded DOWN to 16 bytes; vectors [v_begin, v_end) are done
+// here, and the launcher keeps v_begin >= 1 and v_end <= nvec - 1 so that both aligned loads
+// stay inside the caller's buffers (the first and last 8 elements go the element-wise way).
+__device__ __forceinline__ u32x4 funnel16(u32x4 lo, u32x4 hi, unsigned phase)
+{
+    uint32_t w0 = lo.x, w1 = lo.y, w2 = lo.z, w3 = lo.w, w4 = hi.x, w5 = hi.y, w6 = hi.z, w7 = hi.w;
+    if (phase & 4) { w0 = w1; w1 = w2; w2 = w3; w3 = w4; w4 = w5; w5 = w6; w6 = w7; }
+    if (phase & 8) { w0 = w2; w1 = w3; w2 = w4; w3 = w5; w4 = w6; }
+    u32x4 out = {w0, w1, w2, w3};
+    if (phase & 2) {
+        out.x = (w0 >> 16) | (w1 << 16);
+        out.y = (w1 >> 16) | (w2 << 16);
+        out.z = (w2 >> 16) | (w3 << 16);
+        out.w = (w3 >> 16) | (w4 << 16);
+    }
+    return out;
+}
+
+template <int P, bool ACCUM, bool SA, typename Tab>
+__global__ __launch_bounds__(kRsaBlock) void rsa_shift_kernel(
+    float* __restrict__ acc, Tab g, int p, unsigned phase, size_t v_begin, size_t v_end)
+{
+    const size_t stride = (size_t)gridDim.x * kRsaBlock;
+    for (size_t i = v_begin + (size_t)blockIdx.x * kRsaBlock + threadIdx.x; i < v_end; i += stride) {
+        f32x4 a0 = {0.0f, 0.0f, 0.0f, 0.0f}, a1 = a0;
+        if (ACCUM) {
+            a0 = ld<SA>((const f32x4*)acc + 2 * i);
+            a1 = ld<SA>((const f32x4*)acc + 2 * i + 1);
+        }
+        float s[8];
+        constexpr int B = P > 0 ? P : 16;
+        for (int q0 = 0; q0 < p; q0 += B) {
+            u32x4 lo[B], hi[B];
+            #pragma unroll
+            for (int b = 0; b < B; ++b) {
+                if (q0 + b < p) {
+                    lo[b] = ((const u32x4*)g.ptr[q0 + b])[i];
+                    hi[b] = ((const u32x4*)g.ptr[q0 + b])[i + 1];
+                }
+            }
+            #pragma unroll
+            for (int b = 0; b < B; ++b) {
+                if (q0 + b < p) {
+                    const u32x4 v = funnel16(lo[b], hi[b], phase);
+                    if (q0 + b == 0) {
+                        #pragma unroll
+                        for (int e = 0; e < 4; ++e) { s[2 * e] = bf16_lo(v[e]); s[2 * e + 1] = bf16_hi(v[e]); }
+                    } else {
+                        #pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            s[2 * e] = s[2 * e] + bf16_lo(v[e]);
+                            s[2 * e + 1] = s[2 * e + 1] + bf16_hi(v[e]);
+                        }
+                    }
+                }
+            }
+        }
+        f32x4 o0 = {a0.x + s[0], a0.y + s[1], a0.z + s[2], a0.w + s[3]};
+        f32x4 o1 = {a1.x + s[4], a1.y + s[5], a1.z + s[6], a1.w + s[7]};
+        st<SA>((f32x4*)acc + 2 * i, o0);
+        st<SA>((f32x4*)acc + 2 * i + 1, o1);
+    }
+}
+
 // Coalesced form (many separately sharded tensors in one launch): workgroup x works on tile
 // x - tile_begin[t] of segment t; a lane owns 8 consecutive elements of the segment, the last
 // lane of a segment finishes a ragged end element by element.
@@ -882,12 +951,50 @@ int launch_reorder(void* dst, const PtrTable& src, size_t n_valid_bytes, size_t 
     return launch_status();
 }
 
+namespace {
+void rsa_scalar_launch(float* acc, const PtrTable& g, int p, size_t first, size_t end, bool accumulate,
+                       unsigned blocks, hipStream_t st)
+{
+    if (accumulate)
+        hipLaunchKernelGGL(rsa_scalar_kernel<true>, dim3(blocks), dim3(kBlock), 0, st, acc, g, p, first, end);
+    else
+        hipLaunchKernelGGL(rsa_scalar_kernel<false>, dim3(blocks), dim3(kBlock), 0, st, acc, g, p, first, end);
+}
+}  // namespace
+
+// grad_phase: 0 = every buffer 16-byte aligned (with an aligned accumulator); 2..14 = every
+// gradient buffer starts that many bytes into a 16-byte line (accumulator aligned); -1 = no
+// common alignment: element-wise kernel.
 int launch_reduce_scatter_accum(float* acc, const PtrTable& g, size_t count, int p, bool accumulate,
-                                bool vec16, void* stream)
+                                int grad_phase, void* stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    const size_t nvec = vec16 ? count / 8 : 0;
     unsigned blocks = 0;
+    const size_t nvec_all = count / 8;
+    if (grad_phase > 0 && nvec_all >= 3) {
+        // middle vectors through the shift kernel, first and last 8 (+ tail) elements one by one
+        PtrTable down{};
+        for (int q = 0; q < p; ++q) down.ptr[q] = (const char*)g.ptr[q] - grad_phase;
+        const size_t v_begin = 1, v_end = nvec_all - 1;
+        if (int e = grid_for(v_end - v_begin, kRsaBlock, MICS_RSA_BPC, &blocks)) return e;
+        dispatch2(accumulate, stream_acc(count), [&](auto A, auto SA) {
+            if (p == 16)
+                hipLaunchKernelGGL((rsa_shift_kernel<16, A.value, SA.value, SmallTable<16>>), dim3(blocks),
+                                   dim3(kRsaBlock), 0, st, acc, small<16>(down), p, (unsigned)grad_phase,
+                                   v_begin, v_end);
+            else
+                hipLaunchKernelGGL((rsa_shift_kernel<0, A.value, SA.value, PtrTable>), dim3(blocks),
+                                   dim3(kRsaBlock), 0, st, acc, down, p, (unsigned)grad_phase, v_begin, v_end);
+        });
+        if (int e = launch_status()) return e;
+        if (int e = grid_for(8, kBlock, kTailBpc, &blocks)) return e;
+        rsa_scalar_launch(acc, g, p, 0, 8, accumulate, blocks, st);
+        if (int e = launch_status()) return e;
+        if (int e = grid_for(count - v_end * 8, kBlock, kTailBpc, &blocks)) return e;
+        rsa_scalar_launch(acc, g, p, v_end * 8, count, accumulate, blocks, st);
+        return launch_status();
+    }
+    const size_t nvec = grad_phase == 0 ? nvec_all : 0;
     if (nvec) {
         if (int e = grid_for(nvec, kRsaBlock, MICS_RSA_BPC, &blocks)) return e;
         switch (p) {
@@ -908,12 +1015,7 @@ int launch_reduce_scatter_accum(float* acc, const PtrTable& g, size_t count, int
     const size_t first = nvec * 8;
     if (first < count) {
         if (int e = grid_for(count - first, kBlock, kTailBpc, &blocks)) return e;
-        if (accumulate)
-            hipLaunchKernelGGL(rsa_scalar_kernel<true>, dim3(blocks), dim3(kBlock), 0, st, acc, g, p,
-                               first, count);
-        else
-            hipLaunchKernelGGL(rsa_scalar_kernel<false>, dim3(blocks), dim3(kBlock), 0, st, acc, g, p,
-                               first, count);
+        rsa_scalar_launch(acc, g, p, first, count, accumulate, blocks, st);
         if (int e = launch_status()) return e;
     }
     return 0;

@@ -575,3 +575,27 @@ def test_capped_grids_give_the_same_results(orc, gen):
             assert np.array_equal(pb.numpy(), pbr) and pb.guards_intact()
     finally:
         mics.mics_set_blocks_per_cu(0)
+
+
+# ---- rank buffers that share a non-zero offset inside their 16-byte lines ---------------------------------
+
+@pytest.mark.parametrize("p,off,count", [(16, 1, 50000), (16, 2, 50001), (16, 3, 49999), (16, 4, 50000),
+                                         (16, 5, 40007), (16, 6, 40000), (16, 7, 65536 + 9), (4, 7, 30000),
+                                         (40, 5, 20011), (16, 3, 23), (16, 3, 24), (16, 3, 31), (2, 1, 8)])
+def test_reduce_scatter_accum_with_commonly_shifted_buffers(orc, gen, p, off, count):
+    """elem_offset = g*S with an odd S: every buffer starts `off` elements into a 16-byte line
+    while the accumulator is aligned (funnel-shift kernel); bit-exact like the aligned path."""
+    total = off + count + 11
+    tab = gen.normal_table(1e-3, "bf16")
+    acc = Guarded(count, np.float32)
+    ref = np.full(count, np.nan, np.float32)
+    for t in range(2):
+        host = [gen.fill_host(gen.stream_key(1100 + off, gen.ROLE_GRAD, 0, t, q), 0, total, tab)
+                for q in range(p)]
+        dev = [Guarded(total, np.uint16, fill=h) for h in host]
+        mics.mics_reduce_scatter_accum(acc.t, [d.t for d in dev], off, count, t > 0)
+        torch.cuda.synchronize()
+        orc.reduce_scatter_accum(ref, host, off, t > 0)
+        assert all(d.guards_intact() for d in dev)
+    assert np.array_equal(acc.numpy().view(np.uint32), ref.view(np.uint32))
+    assert acc.guards_intact()
