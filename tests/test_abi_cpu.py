@@ -145,3 +145,16 @@ def test_launch_knob_range():
         mics.mics_set_blocks_per_cu(4097)
     with pytest.raises(mics.MicsError):
         mics.mics_set_blocks_per_cu(-1)
+
+
+def test_header_is_valid_c99_and_cxx(tmp_path):
+    import subprocess
+    c = tmp_path / "use.c"
+    c.write_text('#include "mics.h"\nint f(void) { mics_segment s = {1, 1, 0, 0}; (void)s; '
+                 'return mics_version() + MICS_MAX_GROUP + MICS_ERR_HIP + MICS_DTYPE_F32; }\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", f"-I{inc}", str(c)],
+                   check=True)
+    cxx = tmp_path / "use.cpp"
+    cxx.write_text(c.read_text())
+    subprocess.run(["g++", "-std=c++17", "-Wall", "-Werror", "-fsyntax-only", f"-I{inc}", str(cxx)], check=True)
