@@ -241,6 +241,19 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
+    # a plain copy of the layer (the reorder with p = k = 1) as this chip's practical ceiling for
+    # a one-read-one-write stream; reported beside the nominal peak, outside the timed steps
+    copy_gbps = None
+    if not args.coalesced:
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        mics.mics_hier_gather_reorder(F, [W], N, N, 1, 1, 2, stream=sh)
+        c0.record(stream)
+        for _ in range(5):
+            mics.mics_hier_gather_reorder(F, [W], N, N, 1, 1, 2, stream=sh)
+        c1.record(stream)
+        c1.synchronize()
+        copy_gbps = 5 * 4 * N / (c0.elapsed_time(c1) * 1e-3) / 1e9
+
     for marks in all_marks:
         for i, name in enumerate(("a1", "a2", "a3", "a4")):
             ev[name].append(marks[i].elapsed_time(marks[i + 1]))
@@ -272,6 +285,8 @@ def main():
         "dtype": f"{args.grad_dtype} in / f32 accumulate",
         "data": "synthetic",
         "pct_of_peak_hbm": round(100.0 * gbps / PEAK_HBM_GBPS, 2),
+        "plain_copy_GBps": round(copy_gbps, 1) if copy_gbps else None,
+        "pct_of_plain_copy": round(100.0 * gbps / copy_gbps, 2) if copy_gbps else None,
         "elements_per_s": round(count / (ms_step * 1e-3), 1),
         "config": {
             "workload": f"{cfg.name}: one transformer layer h={cfg.name[1:]} N={N}, p={p} "
