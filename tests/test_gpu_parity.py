@@ -599,3 +599,43 @@ def test_reduce_scatter_accum_with_commonly_shifted_buffers(orc, gen, p, off, co
         assert all(d.guards_intact() for d in dev)
     assert np.array_equal(acc.numpy().view(np.uint32), ref.view(np.uint32))
     assert acc.guards_intact()
+
+
+def test_calls_on_two_streams_ordered_by_events(orc, gen):
+    """The paper keeps communication and computation on separate streams and orders them with
+    events instead of device-wide synchronisation (Section 4).  Here a gather reorder runs on one
+    stream while reduce-scatter-accumulates run on another; the Adam step waits for an event
+    recorded after the last reduction.  No call synchronises, results are as in a serial run."""
+    p, k, S = 8, 4, 300_000
+    tab = gen.normal_table(1e-3, "bf16")
+    shards = [tagged(gen, 4000 + g, S, np.uint16) for g in range(p)]
+    T = [upload(orc.stage1_gather(shards, k, l)) for l in range(k)]
+    flat = torch.zeros(p * S, dtype=torch.int16, device="cuda:0")
+    host = [[gen.fill_host(gen.stream_key(1200, gen.ROLE_GRAD, 0, t, q), 0, S, tab) for q in range(p)] for t in range(4)]
+    dev = [[upload(h) for h in step] for step in host]
+    acc = torch.empty(S, dtype=torch.float32, device="cuda:0")
+    w0 = gen.fill_host(gen.stream_key(1200, gen.ROLE_MASTER), 0, S, gen.normal_table(0.02, "f32"))
+    w, m, v = upload(w0.copy()), torch.zeros(S, device="cuda:0"), torch.zeros(S, device="cuda:0")
+    pb = torch.empty(S, dtype=torch.int16, device="cuda:0")
+    torch.cuda.synchronize()
+
+    comm, comp = torch.cuda.Stream(), torch.cuda.Stream()
+    done = torch.cuda.Event()
+    for rep in range(3):                      # several rounds in flight at once
+        mics.mics_hier_gather_reorder(flat, T, p * S, S, p, k, 2, stream=comm)
+    for t in range(4):
+        mics.mics_reduce_scatter_accum(acc, dev[t], 0, S, t > 0, stream=comp)
+    done.record(comp)
+    comm.wait_event(done)                     # the update is enqueued behind the gathers, after the reductions
+    mics.mics_adam_shard(w, m, v, pb, acc, S, step=1, stream=comm, **HP)
+    comm.synchronize()
+
+    assert np.array_equal(flat.cpu().numpy().view(np.uint16), np.concatenate(shards))
+    ref = np.empty(S, np.float32)
+    for t in range(4):
+        orc.reduce_scatter_accum(ref, host[t], 0, t > 0)
+    assert np.array_equal(acc.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+    wr, mr, vr = w0.copy(), np.zeros(S, np.float32), np.zeros(S, np.float32)
+    pbr = orc.adam_shard(wr, mr, vr, ref, step=1, f32=True, **HP)
+    assert np.array_equal(w.cpu().numpy().view(np.uint32), wr.view(np.uint32))
+    assert np.array_equal(pb.cpu().numpy().view(np.uint16), pbr)
