@@ -47,6 +47,9 @@ def parse_args():
     ap.add_argument("--grad-dtype", choices=["bf16", "f16", "f32"], default="bf16",
                     help="storage format of the gradient buffers the reduce-scatter-accumulate reads "
                          "(rank view, flat layout)")
+    ap.add_argument("--param-dtype", choices=["bf16", "f32"], default="bf16",
+                    help="f32: plain float32 training -- the gathered parameter has 4-byte elements and "
+                         "the Adam step writes no bf16 copy")
     ap.add_argument("--fused", action="store_true",
                     help="run the replica average and the Adam step as one fused call "
                          "(mics_replica_average_adam_shard): 4r+26 instead of 4r+34 bytes per element")
@@ -94,7 +97,10 @@ def main():
     if cfg.outlier_frac:
         tab_go = torch.from_numpy(
             synth.normal_table(cfg.sigma_grad * cfg.outlier_scale, "bf16").view(np.int16)).to(dev)
-    tab_p = torch.from_numpy(synth.normal_table(cfg.sigma_master, "bf16").view(np.int16)).to(dev)
+    pf32 = args.param_dtype == "f32"
+    pb, p_dt = (4, torch.float32) if pf32 else (2, torch.int16)      # parameter element bytes / dtype
+    tab_p = (torch.from_numpy(synth.normal_table(cfg.sigma_master, "f32")).to(dev) if pf32 else
+             torch.from_numpy(synth.normal_table(cfg.sigma_master, "bf16").view(np.int16)).to(dev))
     tab_w = torch.from_numpy(synth.normal_table(cfg.sigma_master, "f32")).to(dev)
     sigma_acc = cfg.sigma_grad * (p * s) ** 0.5
     tab_a = torch.from_numpy(synth.normal_table(sigma_acc, "f32")).to(dev)
@@ -104,14 +110,14 @@ def main():
                           outl.data_ptr() if outl is not None else 0, frac, sh)
 
     nodes = p // k
-    F = torch.empty(N, dtype=torch.int16, device=dev)
+    F = torch.empty(N, dtype=p_dt, device=dev)
     if not args.coalesced:
         # a1: the gathered-but-unordered parameter W = [T_0 .. T_{k-1}], T_l = [C_l, C_{k+l}, ...]
-        W = torch.empty(n_pad, dtype=torch.int16, device=dev)
+        W = torch.empty(n_pad, dtype=p_dt, device=dev)
         for g in range(p):
             j, l = divmod(g, k)
             slot = (l * nodes + j) * S
-            fill(W[slot:slot + S], synth.stream_key(cfg.seed, synth.ROLE_PARAM, 0, 0, g), 0, tab_p, 2)
+            fill(W[slot:slot + S], synth.stream_key(cfg.seed, synth.ROLE_PARAM, 0, 0, g), 0, tab_p, pb)
         T_views = [W[l * nodes * S:(l + 1) * nodes * S] for l in range(k)]
 
         # a2: per micro-step, p gradient buffers covering the elements this call owns
@@ -150,12 +156,12 @@ def main():
         lay = synth.coalesced_layout([n for _, n in synth.layer_tensors(h)], p, k, align=8)
         assert lay.shard_off[-1] == S and lay.flat_off[-1] == N
         # a1: k separate stage-1 buffers, tensor after tensor, each holding that tensor's p/k chunks
-        T_views = [torch.empty(lay.stage1_off[-1], dtype=torch.int16, device=dev) for _ in range(k)]
+        T_views = [torch.empty(lay.stage1_off[-1], dtype=p_dt, device=dev) for _ in range(k)]
         for t, St in enumerate(lay.S):
             for g in range(p):
                 j, l = divmod(g, k)
                 at = lay.stage1_off[t] + j * St
-                fill(T_views[l][at:at + St], synth.stream_key(cfg.seed, synth.ROLE_PARAM, t, 0, g), 0, tab_p, 2)
+                fill(T_views[l][at:at + St], synth.stream_key(cfg.seed, synth.ROLE_PARAM, t, 0, g), 0, tab_p, pb)
         reorder_segs = mics._segments(lay.reorder_segments())
         # a2: every rank's full gradient buffer (all tensors, p*S_t each); the rank reads its slices
         n_sets = min(s, 4)
@@ -181,7 +187,7 @@ def main():
     fill(master, synth.stream_key(cfg.seed, synth.ROLE_MASTER), offset, tab_w, 4)
     exp_avg = torch.zeros(count, dtype=torch.float32, device=dev)
     exp_avg_sq = torch.zeros(count, dtype=torch.float32, device=dev)
-    param = torch.empty(count, dtype=torch.int16, device=dev)
+    param = None if pf32 else torch.empty(count, dtype=torch.int16, device=dev)
     hp = dict(lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps, weight_decay=cfg.weight_decay)
     torch.cuda.synchronize()
 
@@ -198,9 +204,9 @@ def main():
         if timed:
             marks[0].record(stream)
         if args.coalesced:
-            mics.mics_hier_gather_reorder_coalesced(F, T_views, reorder_segs, p, k, 2, stream=sh)
+            mics.mics_hier_gather_reorder_coalesced(F, T_views, reorder_segs, p, k, pb, stream=sh)
         else:
-            mics.mics_hier_gather_reorder(F, T_views, N, S, p, k, 2, stream=sh)
+            mics.mics_hier_gather_reorder(F, T_views, N, S, p, k, pb, stream=sh)
         if timed:
             marks[1].record(stream)
         for t in range(s):
@@ -230,7 +236,7 @@ def main():
         if args.coalesced:
             print("--calibration-copy is for the flat layout", file=sys.stderr)
             sys.exit(2)
-        mics.mics_hier_gather_reorder(F, [W], N, N, 1, 1, 2, stream=sh)
+        mics.mics_hier_gather_reorder(F, [W], N, N, 1, 1, pb, stream=sh)
         torch.cuda.synchronize()
     for it in range(1, args.warmup + 1):
         step(it, False)
@@ -246,13 +252,13 @@ def main():
     copy_gbps = None
     if not args.coalesced:
         c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        mics.mics_hier_gather_reorder(F, [W], N, N, 1, 1, 2, stream=sh)
+        mics.mics_hier_gather_reorder(F, [W], N, N, 1, 1, pb, stream=sh)
         c0.record(stream)
         for _ in range(5):
-            mics.mics_hier_gather_reorder(F, [W], N, N, 1, 1, 2, stream=sh)
+            mics.mics_hier_gather_reorder(F, [W], N, N, 1, 1, pb, stream=sh)
         c1.record(stream)
         c1.synchronize()
-        copy_gbps = 5 * 4 * N / (c0.elapsed_time(c1) * 1e-3) / 1e9
+        copy_gbps = 5 * 2 * pb * N / (c0.elapsed_time(c1) * 1e-3) / 1e9
 
     for marks in all_marks:
         for i, name in enumerate(("a1", "a2", "a3", "a4")):
@@ -261,11 +267,12 @@ def main():
     ms_step = wall * 1e3 / args.steps
 
     # ---- algorithmic bytes (what the method must move) ---------------------------------------
-    b_a1 = 2 * 2 * N
+    b_a1 = 2 * pb * N
     b_a2_first, b_a2_next = count * (gb * p + 4), count * (gb * p + 8)
     b_a2 = b_a2_first + (s - 1) * b_a2_next
     b_a3 = 0 if args.fused else count * (4 * r + 4)
-    b_a4 = count * (4 * r + 26) if args.fused else count * 30
+    out_a4 = 12 if pf32 else 14                      # master, m, v (+ bf16 parameter)
+    b_a4 = count * (4 * r + 12 + out_a4) if args.fused else count * (16 + out_a4)
     b_step = b_a1 + b_a2 + b_a3 + b_a4
     gbps = b_step / (ms_step * 1e-3) / 1e9
     a2_launch_ms = ms["a2"] / s
@@ -282,7 +289,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": f"{args.grad_dtype} in / f32 accumulate",
+        "dtype": f"{args.grad_dtype} in / f32 accumulate" + (", f32 parameters" if pf32 else ""),
         "data": "synthetic",
         "pct_of_peak_hbm": round(100.0 * gbps / PEAK_HBM_GBPS, 2),
         "plain_copy_GBps": round(copy_gbps, 1) if copy_gbps else None,
