@@ -50,6 +50,10 @@ def parse_args():
     ap.add_argument("--param-dtype", choices=["bf16", "f32"], default="bf16",
                     help="f32: plain float32 training -- the gathered parameter has 4-byte elements and "
                          "the Adam step writes no bf16 copy")
+    ap.add_argument("--gathers-per-microstep", type=int, default=0,
+                    help="run this many extra gather reorders before every reduce-scatter-accumulate, as "
+                         "a training run does (parameters are gathered in the forward and in the backward "
+                         "pass of every micro-step); the default step gathers once")
     ap.add_argument("--fused", action="store_true",
                     help="run the replica average and the Adam step as one fused call "
                          "(mics_replica_average_adam_shard): 4r+26 instead of 4r+34 bytes per element")
@@ -210,6 +214,11 @@ def main():
         if timed:
             marks[1].record(stream)
         for t in range(s):
+            for _ in range(args.gathers_per_microstep):
+                if args.coalesced:
+                    mics.mics_hier_gather_reorder_coalesced(F, T_views, reorder_segs, p, k, pb, stream=sh)
+                else:
+                    mics.mics_hier_gather_reorder(F, T_views, N, S, p, k, pb, stream=sh)
             if args.coalesced:
                 mics.mics_reduce_scatter_accum_coalesced(acc, grad_tables[t], reduce_segs, t > 0, stream=sh)
             elif args.grad_dtype != "bf16":
@@ -273,10 +282,12 @@ def main():
     b_a3 = 0 if args.fused else count * (4 * r + 4)
     out_a4 = 12 if pf32 else 14                      # master, m, v (+ bf16 parameter)
     b_a4 = count * (4 * r + 12 + out_a4) if args.fused else count * (16 + out_a4)
-    b_step = b_a1 + b_a2 + b_a3 + b_a4
+    extra_gathers = args.gathers_per_microstep * s
+    b_step = b_a1 * (1 + extra_gathers) + b_a2 + b_a3 + b_a4
     gbps = b_step / (ms_step * 1e-3) / 1e9
-    a2_launch_ms = ms["a2"] / s
-    a2_gbps = (b_a2 / s) / (a2_launch_ms * 1e-3) / 1e9
+    # with interleaved gathers the a2 bracket holds them too: bytes and launches of both
+    a2_launch_ms = ms["a2"] / (s + extra_gathers)
+    a2_gbps = ((b_a2 + extra_gathers * b_a1) / (s + extra_gathers)) / (a2_launch_ms * 1e-3) / 1e9
 
     result = {
         "metric": "effective HBM GB/s per shard step",
@@ -300,13 +311,14 @@ def main():
                         f"({nodes} nodes x k={k}), r={r}, s={s}, {args.view} view "
                         f"({count} elements per reduce/average/Adam call)"
                         + (", coalesced: 16 separately sharded tensors" if args.coalesced else ""),
-            "view": args.view, "coalesced": bool(args.coalesced), "fused_average_adam": bool(args.fused), "N": N, "S": S, "p": p, "k": k, "r": r, "s": s,
+            "view": args.view, "coalesced": bool(args.coalesced), "fused_average_adam": bool(args.fused),
+            "gathers_per_microstep": args.gathers_per_microstep, "N": N, "S": S, "p": p, "k": k, "r": r, "s": s,
             "algorithmic_bytes_per_step": b_step,
         },
         "kernels": {
             name: {"ms": round(ms[name], 4),
                    "GB/s": round(b / (ms[name] * 1e-3) / 1e9, 1)}
-            for name, b in (("a1", b_a1), ("a2", b_a2), ("a3", b_a3), ("a4", b_a4))
+            for name, b in (("a1", b_a1), ("a2", b_a2 + extra_gathers * b_a1), ("a3", b_a3), ("a4", b_a4))
             if not (args.fused and name == "a3")
         },
         "roofline": {
