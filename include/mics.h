@@ -27,20 +27,30 @@
  *   - Data pointers are DEVICE pointers on the current HIP device.  Pointer
  *     tables (`const T* const*`) are HOST arrays of device pointers; they are
  *     read during the call and may be freed or reused as soon as it returns.
- *   - The caller owns every buffer.  The library allocates no memory, keeps no
- *     state between calls (apart from the thread-local error text) and never
- *     synchronises: each call validates its arguments on the host, enqueues
- *     its kernel(s) on `stream` (a hipStream_t passed as void*; NULL = the
- *     default stream) and returns.  Work is ordered by that stream.
+ *   - The caller owns every buffer.  The library allocates no device memory
+ *     and never synchronises: each call validates its arguments on the host,
+ *     enqueues its kernel(s) on `stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream) and returns.  Work is ordered by that stream.
+ *     No kernel uses scratch memory beyond the caller's buffers.
+ *   - State between calls: the thread-local error text, and the two
+ *     process-wide measurement knobs of mics_tuning.h (launch shape, cache-hint
+ *     threshold), which never change a result.  Nothing else.
  *   - Arguments are validated before the first HIP call, so every argument
- *     error is reported without a GPU.  On error nothing is enqueued.
+ *     error is reported without a GPU, and on an argument error nothing is
+ *     enqueued.  MICS_ERR_HIP reports the status of the failed launch call
+ *     itself (an earlier, unrelated HIP error of the thread is neither reported
+ *     nor cleared); every entry point issues a single launch, except the
+ *     coalesced ones, which issue one launch per 48 tensors and may have
+ *     enqueued earlier launches when a later one fails.
  *   - Return value: MICS_OK or a negative MICS_ERR_*; mics_last_error() gives
  *     the text for the calling thread's most recent failure.
  *   - bf16 values travel as uint16_t bit patterns (upper half of a binary32).
- *   - Pointers must be aligned to their element size.  16-byte alignment of
- *     every buffer (and, for the reorder, a shard size that is a multiple of
- *     16 bytes) selects the full-speed kernels; anything less aligned is still
- *     computed correctly by slower kernels.
+ *   - Pointers must be aligned to their element size; that is all the
+ *     element-wise calls (reduce, average, Adam) need for full speed, except
+ *     that bf16/fp16 gradient buffers of one call should all start at even or
+ *     all at odd element addresses (otherwise about 20 % slower).  The reorder
+ *     runs at copy speed when every buffer and the shard size are multiples
+ *     of 16 bytes and through an LDS-staged kernel (about 10 % slower) otherwise.
  *   - Buffers of one call must not overlap unless stated.
  */
 #ifndef MICS_H
@@ -206,9 +216,10 @@ typedef struct mics_segment {
  * index x < numel_t, with g = x div S_t, i = x mod S_t, j = g div k, l = g mod k,
  *     dst_flat[dst_offset_t + x] = stage1_bufs[l][src_offset_t + j*S_t + i].
  * Tensor t occupies (p/k)*S_t elements from src_offset_t in every stage-1 buffer and numel_t
- * elements from dst_offset_t in dst_flat; regions of different tensors must not overlap.
- * segs is a HOST array.  Tensors whose addresses and shard sizes are multiples of 16 bytes
- * share one launch (per 48 tensors); any other tensor is moved by a launch of its own.
+ * elements from dst_offset_t in dst_flat; the destination regions of different tensors must not
+ * overlap (checked: MICS_ERR_INVALID_ARG).  segs is a HOST array.  Tensors whose addresses and
+ * shard sizes are multiples of 16 bytes share one launch per 48 of them, all other tensors
+ * another launch per 48: a layer of 16 tensors is moved by at most two launches.
  */
 int mics_hier_gather_reorder_coalesced(void* dst_flat, const void* const* stage1_bufs,
                                        const mics_segment* segs, int n_segs, int p, int k,
@@ -221,18 +232,12 @@ int mics_hier_gather_reorder_coalesced(void* dst_flat, const void* const* stage1
  * same arithmetic and order as mics_reduce_scatter_accum.  For rank g of a partition group
  * whose gradient buffers hold tensor t at offset o_t (p*S_t elements) and whose shard buffer
  * holds it at offset a_t: numel = S_t, src_offset = o_t + g*S_t, dst_offset = a_t.
+ * The accumulator regions of different tensors must not overlap (checked).  One launch per
+ * 48 tensors, whatever their alignment.
  */
 int mics_reduce_scatter_accum_coalesced(float* acc, const uint16_t* const* grads_bf16,
                                         const mics_segment* segs, int n_segs, int p,
                                         int accumulate, void* stream);
-
-/*
- * Launch-shape knob for measurements (not part of the method): sets how many
- * workgroups per compute unit the streaming kernels of later calls launch at
- * most; 0 restores the built-in choice.  Process-wide.  Returns MICS_OK or
- * MICS_ERR_INVALID_ARG (negative or > 4096).
- */
-int mics_set_blocks_per_cu(int blocks_per_cu);
 
 #ifdef __cplusplus
 }

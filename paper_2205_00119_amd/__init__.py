@@ -1,7 +1,7 @@
 """MI355X-native per-GPU data path of MiCS partitioned data parallelism.
 
 Thin ctypes binding over ``libmics.so`` (see ``include/mics.h`` for the contract of each
-call).  The functions here only marshal arguments -- device pointers, sizes and the
+call, ``include/mics_tuning.h`` for the two measurement knobs).  The functions here only marshal arguments -- device pointers, sizes and the
 current HIP stream; every step of the path runs in the library's HIP kernels.  There is
 no CPU fallback: if the library is missing, importing this package fails.
 """
@@ -23,6 +23,7 @@ MICS_MAX_GROUP = 128
 
 EXPORTS = (
     "mics_version", "mics_last_error", "mics_shard_elems", "mics_set_blocks_per_cu",
+    "mics_set_stream_threshold_bytes",
     "mics_hier_gather_reorder", "mics_reduce_scatter_accum", "mics_replica_average",
     "mics_adam_shard", "mics_hier_gather_reorder_coalesced", "mics_reduce_scatter_accum_coalesced",
     "mics_replica_average_adam_shard", "mics_reduce_scatter_accum_typed",
@@ -57,6 +58,8 @@ lib.mics_shard_elems.argtypes = [_sz, _i, _sz]
 lib.mics_shard_elems.restype = _sz
 lib.mics_set_blocks_per_cu.argtypes = [_i]
 lib.mics_set_blocks_per_cu.restype = _i
+lib.mics_set_stream_threshold_bytes.argtypes = [_sz]
+lib.mics_set_stream_threshold_bytes.restype = _i
 lib.mics_hier_gather_reorder.argtypes = [_vp, _vp, _sz, _sz, _i, _i, _i, _vp]
 lib.mics_hier_gather_reorder.restype = _i
 lib.mics_reduce_scatter_accum.argtypes = [_vp, _vp, _sz, _sz, _i, _i, _vp]
@@ -138,6 +141,10 @@ def mics_shard_elems(n: int, p: int, align_elems: int = 8) -> int:
 
 def mics_set_blocks_per_cu(blocks_per_cu: int) -> None:
     _check(lib.mics_set_blocks_per_cu(blocks_per_cu))
+
+
+def mics_set_stream_threshold_bytes(nbytes: int) -> None:
+    _check(lib.mics_set_stream_threshold_bytes(nbytes))
 
 
 def mics_hier_gather_reorder(dst_flat, stage1_bufs: Sequence, n_valid: int, shard_elems: int,

@@ -2,11 +2,16 @@
 // Every check here runs before the first HIP call, so argument errors are
 // reported identically on a machine without a GPU.
 #include "../../include/mics.h"
+#include "../../include/mics_tuning.h"
 #include "internal.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <new>
+#include <utility>
+#include <vector>
 
 namespace {
 
@@ -30,14 +35,29 @@ inline bool overlaps(const void* a, size_t an, const void* b, size_t bn)
     return an && bn && addr(a) < addr(b) + bn && addr(b) < addr(a) + an;
 }
 
-// Running common offset of gradient pointers inside their 16-byte lines: start with -2 (nothing
-// seen; -1 if the accumulator itself is not 16-byte aligned), feed every pointer; the result is
-// the shared offset 0..14, or -1 if the pointers disagree.
-int common_phase(int so_far, const void* ptr)
+// True if two of the destination regions [dst_offset, dst_offset + numel) of the segments share an
+// element.  *bad_a / *bad_b receive the indices of one offending pair.  Returns -1 if the host
+// is out of memory for the sort.
+int regions_overlap(const mics_segment* segs, int n, int* bad_a, int* bad_b)
 {
-    const int ph = (int)(addr(ptr) & 15);
-    if (so_far == -2) return ph;
-    return so_far == ph ? so_far : -1;
+    try {
+        std::vector<std::pair<size_t, int>> order;
+        order.reserve((size_t)n);
+        for (int t = 0; t < n; ++t)
+            if (segs[t].numel) order.emplace_back(segs[t].dst_offset, t);
+        std::sort(order.begin(), order.end());
+        for (size_t i = 1; i < order.size(); ++i) {
+            const mics_segment& prev = segs[order[i - 1].second];
+            if (prev.dst_offset + prev.numel > order[i].first) {
+                *bad_a = order[i - 1].second;
+                *bad_b = order[i].second;
+                return 1;
+            }
+        }
+        return 0;
+    } catch (const std::bad_alloc&) {
+        return -1;
+    }
 }
 
 int hip_fail(const char* what, int err)
@@ -61,7 +81,7 @@ mics::AdamScalars adam_scalars(float lr, float beta1, float beta2, float eps, fl
 
 extern "C" {
 
-int mics_version(void) { return 100; }
+int mics_version(void) { return 200; }
 
 const char* mics_last_error(void) { return g_error; }
 
@@ -78,6 +98,12 @@ int mics_set_blocks_per_cu(int blocks_per_cu)
     if (blocks_per_cu < 0 || blocks_per_cu > 4096)
         return fail(MICS_ERR_INVALID_ARG, "mics_set_blocks_per_cu: %d not in [0, 4096]", blocks_per_cu);
     mics::set_blocks_per_cu(blocks_per_cu);
+    return MICS_OK;
+}
+
+int mics_set_stream_threshold_bytes(size_t bytes)
+{
+    mics::set_stream_threshold_bytes(bytes);
     return MICS_OK;
 }
 
@@ -126,17 +152,21 @@ int mics_hier_gather_reorder(void* dst_flat, const void* const* stage1_bufs,
     return err ? hip_fail(fn, err) : MICS_OK;
 }
 
-int mics_reduce_scatter_accum_typed(float* acc, const void* const* grads, size_t elem_offset,
-                                    size_t count, int p, int accumulate, int grad_dtype,
-                                    void* stream)
+}  // extern "C"
+
+namespace {
+
+// fn / table: the entry point's and its table argument's names, for the error texts.
+int reduce_scatter_accum(const char* fn, const char* table, float* acc, const void* const* grads,
+                         size_t elem_offset, size_t count, int p, int accumulate, int grad_dtype,
+                         void* stream)
 {
-    const char* fn = "mics_reduce_scatter_accum";
     if (grad_dtype != MICS_DTYPE_BF16 && grad_dtype != MICS_DTYPE_F16 && grad_dtype != MICS_DTYPE_F32)
         return fail(MICS_ERR_UNSUPPORTED, "%s: grad_dtype = %d is not bf16, f16 or f32", fn, grad_dtype);
     const size_t gb = grad_dtype == MICS_DTYPE_F32 ? 4 : 2;
     if (p < 1 || p > MICS_MAX_GROUP)
         return fail(MICS_ERR_INVALID_ARG, "%s: p = %d not in [1, %d]", fn, p, MICS_MAX_GROUP);
-    if (!grads) return fail(MICS_ERR_INVALID_ARG, "%s: the gradient table is NULL", fn);
+    if (!grads) return fail(MICS_ERR_INVALID_ARG, "%s: %s is NULL", fn, table);
     if (elem_offset > SIZE_MAX / 4 - count || count > SIZE_MAX / 4)
         return fail(MICS_ERR_INVALID_ARG, "%s: elem_offset + count overflows", fn);
     if (count == 0) return MICS_OK;
@@ -144,33 +174,40 @@ int mics_reduce_scatter_accum_typed(float* acc, const void* const* grads, size_t
     if (!aligned(acc, 4)) return fail(MICS_ERR_ALIGNMENT, "%s: acc not aligned to 4 bytes", fn);
 
     mics::PtrTable tab{};
-    bool vec16 = aligned(acc, 16);
-    int phase = aligned(acc, 16) ? -2 : -1;      // -2: not seen yet, -1: no common phase
     for (int q = 0; q < p; ++q) {
         const void* g = grads[q];
-        if (!g) return fail(MICS_ERR_INVALID_ARG, "%s: grads_bf16[%d] is NULL", fn, q);
+        if (!g) return fail(MICS_ERR_INVALID_ARG, "%s: %s[%d] is NULL", fn, table, q);
         if (!aligned(g, gb))
-            return fail(MICS_ERR_ALIGNMENT, "%s: grads_bf16[%d] not aligned to %zu bytes", fn, q, gb);
+            return fail(MICS_ERR_ALIGNMENT, "%s: %s[%d] not aligned to %zu bytes", fn, table, q, gb);
         const char* first = (const char*)g + elem_offset * gb;
         if (overlaps(acc, count * 4, first, count * gb))
-            return fail(MICS_ERR_INVALID_ARG, "%s: acc overlaps grads_bf16[%d]", fn, q);
-        vec16 = vec16 && aligned(first, 16);
-        phase = common_phase(phase, first);
+            return fail(MICS_ERR_INVALID_ARG, "%s: acc overlaps %s[%d]", fn, table, q);
         tab.ptr[q] = first;
     }
-    int err = grad_dtype == MICS_DTYPE_BF16
-                  ? mics::launch_reduce_scatter_accum(acc, tab, count, p, accumulate != 0, phase, stream)
-                  : mics::launch_reduce_scatter_accum_typed(acc, tab, count, p, accumulate != 0,
-                                                            grad_dtype, vec16, stream);
+    const int kind = grad_dtype == MICS_DTYPE_BF16 ? 0 : grad_dtype == MICS_DTYPE_F16 ? 1 : 2;
+    int err = mics::launch_reduce_scatter_accum(acc, tab, count, p, accumulate != 0, kind, stream);
     return err ? hip_fail(fn, err) : MICS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mics_reduce_scatter_accum_typed(float* acc, const void* const* grads, size_t elem_offset,
+                                    size_t count, int p, int accumulate, int grad_dtype,
+                                    void* stream)
+{
+    return reduce_scatter_accum("mics_reduce_scatter_accum_typed", "grads", acc, grads, elem_offset, count, p,
+                                accumulate, grad_dtype, stream);
 }
 
 int mics_reduce_scatter_accum(float* acc, const uint16_t* const* grads_bf16,
                               size_t elem_offset, size_t count, int p,
                               int accumulate, void* stream)
 {
-    return mics_reduce_scatter_accum_typed(acc, (const void* const*)grads_bf16, elem_offset, count, p,
-                                           accumulate, MICS_DTYPE_BF16, stream);
+    return reduce_scatter_accum("mics_reduce_scatter_accum", "grads_bf16", acc,
+                                (const void* const*)grads_bf16, elem_offset, count, p, accumulate,
+                                MICS_DTYPE_BF16, stream);
 }
 
 int mics_replica_average(float* out, const float* const* acc_copies,
@@ -186,7 +223,6 @@ int mics_replica_average(float* out, const float* const* acc_copies,
     if (!aligned(out, 4)) return fail(MICS_ERR_ALIGNMENT, "%s: out not aligned to 4 bytes", fn);
 
     mics::PtrTable tab{};
-    bool vec16 = aligned(out, 16);
     for (int c = 0; c < r; ++c) {
         const float* a = acc_copies[c];
         if (!a) return fail(MICS_ERR_INVALID_ARG, "%s: acc_copies[%d] is NULL", fn, c);
@@ -196,10 +232,9 @@ int mics_replica_average(float* out, const float* const* acc_copies,
         bool same_as_first = (c == 0 && a == out);
         if (!same_as_first && overlaps(out, count * 4, a, count * 4))
             return fail(MICS_ERR_INVALID_ARG, "%s: out overlaps acc_copies[%d]", fn, c);
-        vec16 = vec16 && aligned(a, 16);
         tab.ptr[c] = a;
     }
-    int err = mics::launch_replica_average(out, tab, count, r, scale, vec16, stream);
+    int err = mics::launch_replica_average(out, tab, count, r, scale, stream);
     return err ? hip_fail(fn, err) : MICS_OK;
 }
 
@@ -220,26 +255,20 @@ int mics_adam_shard(float* master, float* exp_avg, float* exp_avg_sq,
                     fn);
     const void* f32[4] = {master, exp_avg, exp_avg_sq, grad};
     const char* name[4] = {"master", "exp_avg", "exp_avg_sq", "grad"};
-    bool vec16 = true;
     for (int a = 0; a < 4; ++a) {
         if (!aligned(f32[a], 4))
             return fail(MICS_ERR_ALIGNMENT, "%s: %s not aligned to 4 bytes", fn, name[a]);
-        vec16 = vec16 && aligned(f32[a], 16);
         for (int b = a + 1; b < 4; ++b)
             if (overlaps(f32[a], count * 4, f32[b], count * 4))
                 return fail(MICS_ERR_INVALID_ARG, "%s: %s overlaps %s", fn, name[a], name[b]);
         if (param_bf16 && overlaps(f32[a], count * 4, param_bf16, count * 2))
             return fail(MICS_ERR_INVALID_ARG, "%s: param_bf16 overlaps %s", fn, name[a]);
     }
-    if (param_bf16) {
-        if (!aligned(param_bf16, 2))
-            return fail(MICS_ERR_ALIGNMENT, "%s: param_bf16 not aligned to 2 bytes", fn);
-        vec16 = vec16 && aligned(param_bf16, 16);
-    }
+    if (param_bf16 && !aligned(param_bf16, 2))
+        return fail(MICS_ERR_ALIGNMENT, "%s: param_bf16 not aligned to 2 bytes", fn);
 
     const mics::AdamScalars hp = adam_scalars(lr, beta1, beta2, eps, weight_decay, step);
-    int err = mics::launch_adam(master, exp_avg, exp_avg_sq, param_bf16, grad, count, hp, vec16,
-                                stream);
+    int err = mics::launch_adam(master, exp_avg, exp_avg_sq, param_bf16, grad, count, hp, stream);
     return err ? hip_fail(fn, err) : MICS_OK;
 }
 
@@ -296,33 +325,35 @@ int mics_hier_gather_reorder_coalesced(void* dst_flat, const void* const* stage1
         tab.ptr[l] = s;
     }
     if (total == 0) return MICS_OK;
+    int bad_a = 0, bad_b = 0;
+    if (int ov = regions_overlap(segs, n_segs, &bad_a, &bad_b))
+        return ov < 0 ? fail(MICS_ERR_INVALID_ARG, "%s: out of host memory while checking %d segments", fn, n_segs)
+                      : fail(MICS_ERR_INVALID_ARG, "%s: the destination regions of segments %d and %d overlap",
+                             fn, bad_a, bad_b);
 
-    // 16-byte clean tensors are batched; the rest go through the single-tensor path one by one
-    mics::Segment batch[mics::kMaxSegPerLaunch];
-    int nb = 0;
+    // Tensors whose bases, shard size and offsets are 16-byte clean go to the vector kernel, all
+    // others to the LDS-staged kernel: one launch per kMaxSegPerLaunch tensors of either kind.
+    mics::Segment clean[mics::kMaxSegPerLaunch], other[mics::kMaxSegPerLaunch];
+    int nc = 0, no = 0;
     for (int t = 0; t <= n_segs; ++t) {
         const bool last = (t == n_segs);
-        bool batched = false;
         if (!last && segs[t].numel) {
             const mics_segment& sg = segs[t];
-            batched = bases16 && (sg.shard_elems * eb) % 16 == 0 && (sg.src_offset * eb) % 16 == 0 &&
-                      (sg.dst_offset * eb) % 16 == 0;
-            if (batched) {
-                batch[nb].numel = sg.numel; batch[nb].shard_elems = sg.shard_elems;
-                batch[nb].src_offset = sg.src_offset; batch[nb].dst_offset = sg.dst_offset;
-                ++nb;
-            } else {
-                mics::PtrTable one{};
-                for (int l = 0; l < k; ++l) one.ptr[l] = (const char*)tab.ptr[l] + sg.src_offset * eb;
-                int err = mics::launch_reorder((char*)dst_flat + sg.dst_offset * eb, one, sg.numel * eb,
-                                               sg.shard_elems * eb, p, k, false, stream);
-                if (err) return hip_fail(fn, err);
-            }
+            const bool vec16 = bases16 && (sg.shard_elems * eb) % 16 == 0 && (sg.src_offset * eb) % 16 == 0 &&
+                               (sg.dst_offset * eb) % 16 == 0;
+            mics::Segment& slot = vec16 ? clean[nc++] : other[no++];
+            slot.numel = sg.numel; slot.shard_elems = sg.shard_elems;
+            slot.src_offset = sg.src_offset; slot.dst_offset = sg.dst_offset;
         }
-        if (nb == mics::kMaxSegPerLaunch || (last && nb)) {
-            int err = mics::launch_reorder_coalesced(dst_flat, tab, batch, nb, p, k, elem_bytes, stream);
+        if (nc == mics::kMaxSegPerLaunch || (last && nc)) {
+            int err = mics::launch_reorder_coalesced(dst_flat, tab, clean, nc, p, k, elem_bytes, true, stream);
             if (err) return hip_fail(fn, err);
-            nb = 0;
+            nc = 0;
+        }
+        if (no == mics::kMaxSegPerLaunch || (last && no)) {
+            int err = mics::launch_reorder_coalesced(dst_flat, tab, other, no, p, k, elem_bytes, false, stream);
+            if (err) return hip_fail(fn, err);
+            no = 0;
         }
     }
     return MICS_OK;
@@ -355,7 +386,6 @@ int mics_reduce_scatter_accum_coalesced(float* acc, const uint16_t* const* grads
         if (sg.src_offset + sg.numel > src_hi) src_hi = sg.src_offset + sg.numel;
     }
     mics::PtrTable tab{};
-    bool bases16 = aligned(acc, 16);
     for (int q = 0; q < p; ++q) {
         const uint16_t* g = grads_bf16[q];
         if (!g) return fail(MICS_ERR_INVALID_ARG, "%s: grads_bf16[%d] is NULL", fn, q);
@@ -363,32 +393,25 @@ int mics_reduce_scatter_accum_coalesced(float* acc, const uint16_t* const* grads
             return fail(MICS_ERR_ALIGNMENT, "%s: grads_bf16[%d] not aligned to 2 bytes", fn, q);
         if (total && overlaps(acc + dst_lo, (dst_hi - dst_lo) * 4, g + src_lo, (src_hi - src_lo) * 2))
             return fail(MICS_ERR_INVALID_ARG, "%s: acc overlaps grads_bf16[%d]", fn, q);
-        bases16 = bases16 && aligned(g, 16);
         tab.ptr[q] = g;
     }
     if (total == 0) return MICS_OK;
+    int bad_a = 0, bad_b = 0;
+    if (int ov = regions_overlap(segs, n_segs, &bad_a, &bad_b))
+        return ov < 0 ? fail(MICS_ERR_INVALID_ARG, "%s: out of host memory while checking %d segments", fn, n_segs)
+                      : fail(MICS_ERR_INVALID_ARG, "%s: the accumulator regions of segments %d and %d overlap",
+                             fn, bad_a, bad_b);
 
+    // every tensor, whatever its alignment, shares the launch of its batch
     mics::Segment batch[mics::kMaxSegPerLaunch];
     int nb = 0;
     for (int t = 0; t <= n_segs; ++t) {
         const bool last = (t == n_segs);
         if (!last && segs[t].numel) {
             const mics_segment& sg = segs[t];
-            if (bases16 && sg.src_offset % 8 == 0 && sg.dst_offset % 4 == 0) {
-                batch[nb].numel = sg.numel; batch[nb].shard_elems = 0;
-                batch[nb].src_offset = sg.src_offset; batch[nb].dst_offset = sg.dst_offset;
-                ++nb;
-            } else {
-                mics::PtrTable one{};
-                int phase = aligned(acc + sg.dst_offset, 16) ? -2 : -1;
-                for (int q = 0; q < p; ++q) {
-                    one.ptr[q] = (const uint16_t*)tab.ptr[q] + sg.src_offset;
-                    phase = common_phase(phase, one.ptr[q]);
-                }
-                int err = mics::launch_reduce_scatter_accum(acc + sg.dst_offset, one, sg.numel, p,
-                                                            accumulate != 0, phase, stream);
-                if (err) return hip_fail(fn, err);
-            }
+            batch[nb].numel = sg.numel; batch[nb].shard_elems = 0;
+            batch[nb].src_offset = sg.src_offset; batch[nb].dst_offset = sg.dst_offset;
+            ++nb;
         }
         if (nb == mics::kMaxSegPerLaunch || (last && nb)) {
             int err = mics::launch_reduce_coalesced(acc, tab, batch, nb, p, accumulate != 0, stream);
@@ -419,22 +442,17 @@ int mics_replica_average_adam_shard(float* master, float* exp_avg, float* exp_av
         return fail(MICS_ERR_INVALID_ARG, "%s: master, exp_avg and exp_avg_sq must be non-NULL", fn);
     const void* st[3] = {master, exp_avg, exp_avg_sq};
     const char* name[3] = {"master", "exp_avg", "exp_avg_sq"};
-    bool vec16 = true;
     for (int a = 0; a < 3; ++a) {
         if (!aligned(st[a], 4))
             return fail(MICS_ERR_ALIGNMENT, "%s: %s not aligned to 4 bytes", fn, name[a]);
-        vec16 = vec16 && aligned(st[a], 16);
         for (int b = a + 1; b < 3; ++b)
             if (overlaps(st[a], count * 4, st[b], count * 4))
                 return fail(MICS_ERR_INVALID_ARG, "%s: %s overlaps %s", fn, name[a], name[b]);
         if (param_bf16 && overlaps(st[a], count * 4, param_bf16, count * 2))
             return fail(MICS_ERR_INVALID_ARG, "%s: param_bf16 overlaps %s", fn, name[a]);
     }
-    if (param_bf16) {
-        if (!aligned(param_bf16, 2))
-            return fail(MICS_ERR_ALIGNMENT, "%s: param_bf16 not aligned to 2 bytes", fn);
-        vec16 = vec16 && aligned(param_bf16, 16);
-    }
+    if (param_bf16 && !aligned(param_bf16, 2))
+        return fail(MICS_ERR_ALIGNMENT, "%s: param_bf16 not aligned to 2 bytes", fn);
     mics::PtrTable tab{};
     for (int c = 0; c < r; ++c) {
         const float* a = acc_copies[c];
@@ -446,12 +464,11 @@ int mics_replica_average_adam_shard(float* master, float* exp_avg, float* exp_av
                 return fail(MICS_ERR_INVALID_ARG, "%s: %s overlaps acc_copies[%d]", fn, name[b], c);
         if (param_bf16 && overlaps(param_bf16, count * 2, a, count * 4))
             return fail(MICS_ERR_INVALID_ARG, "%s: param_bf16 overlaps acc_copies[%d]", fn, c);
-        vec16 = vec16 && aligned(a, 16);
         tab.ptr[c] = a;
     }
     const mics::AdamScalars hp = adam_scalars(lr, beta1, beta2, eps, weight_decay, step);
     int err = mics::launch_avg_adam(master, exp_avg, exp_avg_sq, param_bf16, tab, r, scale, count, hp,
-                                    vec16, stream);
+                                    stream);
     return err ? hip_fail(fn, err) : MICS_OK;
 }
 

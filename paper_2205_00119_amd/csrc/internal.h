@@ -16,21 +16,22 @@ struct PtrTable {
 };
 
 // Launchers: arguments are already validated.  Each returns 0 or the hipError_t
-// of the failed runtime call (as int) and enqueues on `stream` without waiting.
+// of the failed launch call (as int) and enqueues on `stream` without waiting.
+// Every launcher issues exactly one kernel launch, the coalesced ones one per
+// kMaxSegPerLaunch segments.
 
 // vec16: every source, the destination and the shard size are multiples of 16
 // bytes -> direct 128-bit copy; otherwise the LDS-staged re-phasing kernel.
 int launch_reorder(void* dst, const PtrTable& src, size_t n_valid_bytes,
                    size_t shard_bytes, int p, int k, bool vec16, void* stream);
 
-// grads.ptr[q] already points at element elem_offset of rank q's buffer.  grad_phase: 0 = the
-// accumulator and every gradient pointer are 16-byte aligned; 2..14 = the accumulator is
-// aligned and every gradient pointer sits that many bytes into a 16-byte line; -1 = neither.
+// grads.ptr[q] already points at element elem_offset of rank q's buffer (aligned to its
+// element size; the accumulator to 4 bytes).  kind: 0 bf16, 1 IEEE binary16, 2 binary32.
 int launch_reduce_scatter_accum(float* acc, const PtrTable& grads, size_t count,
-                                int p, bool accumulate, int grad_phase, void* stream);
+                                int p, bool accumulate, int kind, void* stream);
 
 int launch_replica_average(float* out, const PtrTable& copies, size_t count,
-                           int r, float scale, bool vec16, void* stream);
+                           int r, float scale, void* stream);
 
 struct AdamScalars {
     float lr, beta1, beta2, eps, weight_decay;
@@ -40,16 +41,12 @@ struct AdamScalars {
 
 int launch_adam(float* master, float* exp_avg, float* exp_avg_sq,
                 uint16_t* param_bf16, const float* grad, size_t count,
-                const AdamScalars& hp, bool vec16, void* stream);
-
-// kind 1: IEEE binary16 gradients, kind 2: binary32 gradients (bf16 has its own launcher).
-int launch_reduce_scatter_accum_typed(float* acc, const PtrTable& grads, size_t count, int p,
-                                      bool accumulate, int kind, bool vec16, void* stream);
+                const AdamScalars& hp, void* stream);
 
 // Replica average and Adam in one pass (the averaged gradient stays in registers).
 int launch_avg_adam(float* master, float* exp_avg, float* exp_avg_sq, uint16_t* param_bf16,
                     const PtrTable& copies, int r, float scale, size_t count, const AdamScalars& hp,
-                    bool vec16, void* stream);
+                    void* stream);
 
 // Segment records travel in the kernel-argument segment: at most this many per launch.
 constexpr int kMaxSegPerLaunch = 48;
@@ -59,15 +56,18 @@ struct Segment {
     size_t numel, shard_elems, src_offset, dst_offset;
 };
 
-// Every segment satisfies the 16-byte conditions of the vector kernels (the caller routes the
-// others through the single-tensor launchers).  For the reduction, numel = elements to reduce.
+// vec16: every segment satisfies the 16-byte conditions of the vector kernel (bases, shard
+// size and both offsets); otherwise the segments go through the LDS-staged kernel, which
+// takes any element-aligned geometry.
 int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs, int n, int p,
-                             int k, int elem_bytes, void* stream);
+                             int k, int elem_bytes, bool vec16, void* stream);
+// numel = elements to reduce; any element-aligned geometry.
 int launch_reduce_coalesced(float* acc, const PtrTable& grads, const Segment* segs, int n, int p,
                             bool accumulate, void* stream);
 
 // 0 = built-in choice.
 void set_blocks_per_cu(int n);
+void set_stream_threshold_bytes(size_t n);
 
 const char* hip_error_text(int err);
 

@@ -10,6 +10,13 @@
 // MI355X: a lane that owns several vectors a grid stride apart, or a small
 // persistent grid, loses 5-30 % of the bandwidth, stores most of all).
 //
+// Alignment.  gfx950 executes a 128-bit global access at any address.  Measured on MI355X
+// (p = 16 reduce, 50 M and 200 M elements): accesses that are only 4-byte aligned run at the
+// speed of 16-byte aligned ones; 2-byte aligned ones lose about 20 %.  So the element-wise
+// kernels use 128-bit accesses on under-aligned vector types everywhere, a lane that would
+// cross the end of a buffer works element by element inside the same kernel (no tail
+// launches), and only the bf16/fp16 gradient pointers are rounded down to 4 bytes first.
+//
 // Arithmetic rules (they make the results reproducible bit for bit):
 //   - no fused multiply-add (-ffp-contract=off and the pragma below),
 //   - sums in the order the header states,
@@ -32,6 +39,13 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+// The same vectors at the alignment of their elements (see "Alignment" above).
+typedef u32x4 u32x4_a2 __attribute__((aligned(2)));
+typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
+typedef u32x2 u32x2_a2 __attribute__((aligned(2)));
+typedef uint32_t u32_a2 __attribute__((aligned(2)));
+typedef f32x4 f32x4_a4 __attribute__((aligned(4)));
+typedef f32x2 f32x2_a4 __attribute__((aligned(4)));
 
 // Launch shape and cache hints per kernel family; the defaults are the measured best on
 // MI355X for the h = 8192, p = 16 shard shapes.  *_BLOCK = workgroup size, *_BPC = cap on
@@ -58,6 +72,9 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #ifndef MICS_RSA_NTL
 #define MICS_RSA_NTL 1
 #endif
+#ifndef MICS_RSA_BATCH
+#define MICS_RSA_BATCH 16
+#endif
 #ifndef MICS_AVG_BLOCK
 #define MICS_AVG_BLOCK 512
 #endif
@@ -70,6 +87,9 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #ifndef MICS_ADAM_BLOCK
 #define MICS_ADAM_BLOCK 256
 #endif
+#ifndef MICS_FUSED_BLOCK
+#define MICS_FUSED_BLOCK 256
+#endif
 #ifndef MICS_ADAM_BPC
 #define MICS_ADAM_BPC 4096
 #endif
@@ -79,12 +99,29 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #ifndef MICS_ADAM_NTS
 #define MICS_ADAM_NTS 1
 #endif
+// Small messages on large groups (see rsa_kernel): workgroup size of the one-dword-per-lane
+// variant, the loads it keeps in flight, and the largest call (p * count buffer elements)
+// and smallest group it is used for.
+#ifndef MICS_NARROW_BLOCK
+#define MICS_NARROW_BLOCK 64
+#endif
+#ifndef MICS_NARROW_BATCH
+#define MICS_NARROW_BATCH 64
+#endif
+#ifndef MICS_NARROW_MAX_ELEMS
+#define MICS_NARROW_MAX_ELEMS (4u << 20)
+#endif
+#ifndef MICS_NARROW_MIN_P
+#define MICS_NARROW_MIN_P 24
+#endif
 
-constexpr int kBlock = 256;              // element-wise (tail / unaligned) kernels, LDS reorder
+constexpr int kBlock = 256;              // LDS reorder
 constexpr int kReorderBlock = MICS_REORDER_BLOCK;
 constexpr int kRsaBlock = MICS_RSA_BLOCK;
+constexpr int kNarrowBlock = MICS_NARROW_BLOCK;
 constexpr int kAvgBlock = MICS_AVG_BLOCK;
 constexpr int kAdamBlock = MICS_ADAM_BLOCK;
+constexpr int kFusedBlock = MICS_FUSED_BLOCK;
 constexpr bool kReorderNtl = MICS_REORDER_NTL, kReorderNts = MICS_REORDER_NTS;
 constexpr bool kRsaNtl = MICS_RSA_NTL;   // gradient loads; the accumulator's hint is chosen per launch
 constexpr bool kAvgNtl = MICS_AVG_NTL;   // input loads; the output's hint is chosen per launch
@@ -97,24 +134,48 @@ struct SmallTable {
     const void* ptr[N];
 };
 
-template <bool NT, typename V>
-__device__ __forceinline__ V ld(const V* p)
+// Load / store through a pointer whose pointee type carries the alignment (macros, not function
+// templates: a template parameter would drop the typedef's alignment and promise 16 bytes).
+// NT selects the non-temporal form; it is a compile-time constant wherever these are used.
+#define MICS_LD(NT, ptr) ((NT) ? __builtin_nontemporal_load(ptr) : *(ptr))
+#define MICS_ST(NT, ptr, val) \
+    do { if (NT) __builtin_nontemporal_store((val), (ptr)); else *(ptr) = (val); } while (0)
+
+// N consecutive floats at a 4-byte aligned address, as one access.
+template <int N, bool NT>
+__device__ __forceinline__ void ld_f32(float (&a)[N], const float* p)
 {
-    if constexpr (NT) return __builtin_nontemporal_load(p);
-    else return *p;
+    static_assert(N == 1 || N == 2 || N == 4 || N == 8, "");
+    if constexpr (N == 1) {
+        a[0] = MICS_LD(NT, p);
+    } else if constexpr (N == 2) {
+        const f32x2 t = MICS_LD(NT, (const f32x2_a4*)p);
+        a[0] = t.x; a[1] = t.y;
+    } else {
+        #pragma unroll
+        for (int h = 0; h < N / 4; ++h) {
+            const f32x4 t = MICS_LD(NT, (const f32x4_a4*)p + h);
+            a[4 * h] = t.x; a[4 * h + 1] = t.y; a[4 * h + 2] = t.z; a[4 * h + 3] = t.w;
+        }
+    }
 }
 
-template <bool NT, typename V>
-__device__ __forceinline__ void st(V* p, V v)
+template <int N, bool NT>
+__device__ __forceinline__ void st_f32(float* p, const float (&a)[N])
 {
-    if constexpr (NT) __builtin_nontemporal_store(v, p);
-    else *p = v;
+    if constexpr (N == 1) {
+        MICS_ST(NT, p, a[0]);
+    } else if constexpr (N == 2) {
+        const f32x2 t = {a[0], a[1]};
+        MICS_ST(NT, (f32x2_a4*)p, t);
+    } else {
+        #pragma unroll
+        for (int h = 0; h < N / 4; ++h) {
+            const f32x4 t = {a[4 * h], a[4 * h + 1], a[4 * h + 2], a[4 * h + 3]};
+            MICS_ST(NT, (f32x4_a4*)p + h, t);
+        }
+    }
 }
-
-// bf16 -> fp32 is exact: the bf16 bits are the upper half of the fp32 bits.
-__device__ __forceinline__ float bf16_lo(uint32_t pair) { return __uint_as_float(pair << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t pair) { return __uint_as_float(pair & 0xFFFF0000u); }
-__device__ __forceinline__ float bf16_one(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
 // fp32 -> bf16, round to nearest even, two at a time (gfx950 converts a pair
 // in one instruction).  Low half = a, high half = b.
@@ -157,7 +218,7 @@ __global__ __launch_bounds__(kReorderBlock) void reorder_vec_kernel(
     // achieved bandwidth, for loads and even more for stores.
     const size_t stride = (size_t)gridDim.x * kReorderBlock;
     for (size_t i = (size_t)blockIdx.x * kReorderBlock + threadIdx.x; i < nfull; i += stride)
-        st<kReorderNts>(d + i, ld<kReorderNtl>(s + i));
+        MICS_ST(kReorderNts, d + i, MICS_LD(kReorderNtl, s + i));
 
     // ragged end of the logical buffer: fewer than 16 valid bytes remain
     const size_t tail_halves = (valid - nfull * 16) / 2;
@@ -223,12 +284,12 @@ __global__ __launch_bounds__(kSegBlock) void reorder_seg_kernel(
     #pragma unroll
     for (int u = 0; u < MICS_SEG_U; ++u) {
         const size_t i = tile0 + (size_t)u * kSegBlock + threadIdx.x;
-        if (i < nfull) v[u] = ld<kReorderNtl>(s + i);
+        if (i < nfull) v[u] = MICS_LD(kReorderNtl, s + i);
     }
     #pragma unroll
     for (int u = 0; u < MICS_SEG_U; ++u) {
         const size_t i = tile0 + (size_t)u * kSegBlock + threadIdx.x;
-        if (i < nfull) st<kReorderNts>(d + i, v[u]);
+        if (i < nfull) MICS_ST(kReorderNts, d + i, v[u]);
     }
     // ragged end of the tensor: the tile that holds vector index nfull moves the last bytes
     const size_t tail_halves = (valid - nfull * 16) / 2;
@@ -246,14 +307,30 @@ __global__ __launch_bounds__(kSegBlock) void reorder_seg_kernel(
 // its aligned 128-bit destination vector from two LDS vectors shifted by the
 // (workgroup-uniform) phase.  The partial vectors at the two ends of a chunk
 // are moved in 2-byte units.  Global memory is touched only inside the chunk.
+// Like reorder_seg_kernel the kernel serves many tensors per launch: workgroup x
+// moves tile x - tile_begin[t] of chunk blockIdx.y of tensor t (a single tensor is
+// a table of one entry).
 constexpr int kStageVecsPerThread = 4;
 constexpr int kTileVecs = kBlock * kStageVecsPerThread;   // destination vectors per tile
 constexpr int kTileBytes = kTileVecs * 16;
 
+struct LdsSeg {
+    unsigned long long shard_bytes, valid_bytes, src_byte, dst_byte;
+};
+struct LdsSegTable {
+    int n;
+    unsigned tile_begin[kMaxSeg + 1];
+    LdsSeg seg[kMaxSeg];
+};
+
 __global__ __launch_bounds__(kBlock) void reorder_lds_kernel(
-    unsigned char* __restrict__ dst, PtrTable src, size_t shard_bytes, size_t n_valid_bytes, int k)
+    unsigned char* __restrict__ dst, PtrTable src, LdsSegTable tab, int k)
 {
     __shared__ u32x4 stage[kTileVecs + 2];
+    const unsigned x = blockIdx.x;
+    const int t = segment_of(tab.tile_begin, x);
+    const size_t tile = x - tab.tile_begin[t];
+    const size_t shard_bytes = tab.seg[t].shard_bytes, n_valid_bytes = tab.seg[t].valid_bytes;
     const size_t g = blockIdx.y;
     const size_t chunk_begin = g * shard_bytes;
     if (chunk_begin >= n_valid_bytes) return;
@@ -261,249 +338,261 @@ __global__ __launch_bounds__(kBlock) void reorder_lds_kernel(
     if (valid > shard_bytes) valid = shard_bytes;
     const size_t j = g / (size_t)k, l = g % (size_t)k;
 
-    const uintptr_t d_lo = (uintptr_t)dst + chunk_begin;              // chunk in dst
+    const uintptr_t d_lo = (uintptr_t)dst + tab.seg[t].dst_byte + chunk_begin;      // chunk in dst
     const uintptr_t d_hi = d_lo + valid;
-    const uintptr_t s_chunk = (uintptr_t)src.ptr[l] + j * shard_bytes;  // chunk in src
+    const uintptr_t s_chunk = (uintptr_t)src.ptr[l] + tab.seg[t].src_byte + j * shard_bytes;
     const uintptr_t grid0 = d_lo & ~(uintptr_t)15;                     // 16-byte grid of dst
     const size_t ntiles = (d_hi - grid0 + kTileBytes - 1) / kTileBytes;
+    if (tile >= ntiles) return;                                         // uniform per workgroup
     const unsigned phase = (unsigned)((s_chunk - d_lo) & 15);           // even, uniform
     const unsigned dshift = phase >> 2, half = (phase >> 1) & 1;
     const uint16_t* stage_h = (const uint16_t*)stage;
 
-    for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const uintptr_t tile0 = grid0 + tile * kTileBytes;
-        const uintptr_t t_lo = tile0 > d_lo ? tile0 : d_lo;
-        const uintptr_t t_hi = tile0 + kTileBytes < d_hi ? tile0 + kTileBytes : d_hi;
-        const uintptr_t s_lo = s_chunk + (t_lo - d_lo), s_hi = s_chunk + (t_hi - d_lo);
-        const uintptr_t sa = s_lo & ~(uintptr_t)15;
-        const unsigned nsv = (unsigned)(((s_hi + 15) & ~(uintptr_t)15) - sa) / 16;   // <= kTileVecs+1
+    const uintptr_t tile0 = grid0 + tile * kTileBytes;
+    const uintptr_t t_lo = tile0 > d_lo ? tile0 : d_lo;
+    const uintptr_t t_hi = tile0 + kTileBytes < d_hi ? tile0 + kTileBytes : d_hi;
+    const uintptr_t s_lo = s_chunk + (t_lo - d_lo), s_hi = s_chunk + (t_hi - d_lo);
+    const uintptr_t sa = s_lo & ~(uintptr_t)15;
+    const unsigned nsv = (unsigned)(((s_hi + 15) & ~(uintptr_t)15) - sa) / 16;   // <= kTileVecs+1
 
-        for (unsigned v = threadIdx.x; v < nsv; v += kBlock) {
-            const uintptr_t a = sa + (uintptr_t)v * 16;
-            if (a >= s_lo && a + 16 <= s_hi) {
-                stage[v] = *(const u32x4*)a;
-            } else {
-                uint16_t* row = (uint16_t*)&stage[v];
-                for (unsigned h = 0; h < 8; ++h) {
-                    const uintptr_t b = a + 2 * h;
-                    if (b >= s_lo && b < s_hi) row[h] = *(const uint16_t*)b;
-                }
+    for (unsigned v = threadIdx.x; v < nsv; v += kBlock) {
+        const uintptr_t a = sa + (uintptr_t)v * 16;
+        if (a >= s_lo && a + 16 <= s_hi) {
+            stage[v] = MICS_LD(kReorderNtl, (const u32x4*)a);
+        } else {
+            uint16_t* row = (uint16_t*)&stage[v];
+            for (unsigned h = 0; h < 8; ++h) {
+                const uintptr_t b = a + 2 * h;
+                if (b >= s_lo && b < s_hi) row[h] = *(const uint16_t*)b;
             }
         }
-        __syncthreads();
+    }
+    __syncthreads();
 
-        for (unsigned vv = threadIdx.x; vv < kTileVecs; vv += kBlock) {
-            const uintptr_t a = tile0 + (uintptr_t)vv * 16;      // aligned dst address
-            if (a + 16 <= t_lo || a >= t_hi) continue;
-            // byte offset of this vector's source bytes inside the staged range
-            const long o = (long)(a - d_lo) + (long)(s_chunk - sa);   // a may lie below d_lo
-            if (a >= t_lo && a + 16 <= t_hi) {
-                const unsigned o16 = (unsigned)o >> 4;
-                const u32x4 lo = stage[o16], hi = stage[o16 + 1];
-                // shift the 8 staged dwords down by `dshift` dwords (uniform), then by
-                // half a dword if the phase is an odd number of 2-byte units
-                uint32_t w0 = lo.x, w1 = lo.y, w2 = lo.z, w3 = lo.w;
-                uint32_t w4 = hi.x, w5 = hi.y, w6 = hi.z, w7 = hi.w;
-                if (dshift & 1) { w0 = w1; w1 = w2; w2 = w3; w3 = w4; w4 = w5; w5 = w6; w6 = w7; }
-                if (dshift & 2) { w0 = w2; w1 = w3; w2 = w4; w3 = w5; w4 = w6; }
-                u32x4 out = {w0, w1, w2, w3};
-                if (half) {
-                    out.x = (w0 >> 16) | (w1 << 16);
-                    out.y = (w1 >> 16) | (w2 << 16);
-                    out.z = (w2 >> 16) | (w3 << 16);
-                    out.w = (w3 >> 16) | (w4 << 16);
-                }
-                *(u32x4*)a = out;
-            } else {
-                for (unsigned h = 0; h < 8; ++h) {
-                    const uintptr_t b = a + 2 * h;
-                    if (b >= t_lo && b < t_hi) *(uint16_t*)b = stage_h[(o + 2 * (long)h) >> 1];
-                }
+    for (unsigned vv = threadIdx.x; vv < kTileVecs; vv += kBlock) {
+        const uintptr_t a = tile0 + (uintptr_t)vv * 16;      // aligned dst address
+        if (a + 16 <= t_lo || a >= t_hi) continue;
+        // byte offset of this vector's source bytes inside the staged range
+        const long o = (long)(a - d_lo) + (long)(s_chunk - sa);   // a may lie below d_lo
+        if (a >= t_lo && a + 16 <= t_hi) {
+            const unsigned o16 = (unsigned)o >> 4;
+            const u32x4 lo = stage[o16], hi = stage[o16 + 1];
+            // shift the 8 staged dwords down by `dshift` dwords (uniform), then by
+            // half a dword if the phase is an odd number of 2-byte units
+            uint32_t w0 = lo.x, w1 = lo.y, w2 = lo.z, w3 = lo.w;
+            uint32_t w4 = hi.x, w5 = hi.y, w6 = hi.z, w7 = hi.w;
+            if (dshift & 1) { w0 = w1; w1 = w2; w2 = w3; w3 = w4; w4 = w5; w5 = w6; w6 = w7; }
+            if (dshift & 2) { w0 = w2; w1 = w3; w2 = w4; w3 = w5; w4 = w6; }
+            u32x4 out = {w0, w1, w2, w3};
+            if (half) {
+                out.x = (w0 >> 16) | (w1 << 16);
+                out.y = (w1 >> 16) | (w2 << 16);
+                out.z = (w2 >> 16) | (w3 << 16);
+                out.w = (w3 >> 16) | (w4 << 16);
+            }
+            MICS_ST(kReorderNts, (u32x4*)a, out);
+        } else {
+            for (unsigned h = 0; h < 8; ++h) {
+                const uintptr_t b = a + 2 * h;
+                if (b >= t_lo && b < t_hi) *(uint16_t*)b = stage_h[(o + 2 * (long)h) >> 1];
             }
         }
-        __syncthreads();
     }
 }
 
 // ---------------------------------------------------------------------------
 // Step 2a: reduction of the partition-group reduce-scatter, accumulated over
-// micro-steps (Section 3.4).  One lane owns 8 consecutive elements: one
-// 128-bit load per rank buffer, all issued before the first addition.
+// micro-steps (Section 3.4).
+//
+// Gradient formats (KIND): 0 = bf16, 1 = IEEE binary16 (what mixed precision means on GPUs
+// without bf16), 2 = binary32 (plain float32 training).  Widening to binary32 is exact.
+//
+// One kernel for every alignment.  The kernel works in a "virtual" element index space in
+// which element e of every (rounded-down) gradient pointer sits at a 4-byte aligned address
+// whenever e is a multiple of the lane's element count; the call's elements are the virtual
+// range [lead, lead + count), lead = 0 or 1 (1 when the bf16/fp16 pointers had to be rounded
+// down by one element).  A lane owns the virtual elements [EPL*i, EPL*i + EPL): one load per
+// rank buffer, one load and one store of the accumulator (which is then 4-byte aligned at
+// worst).  A lane whose elements are not all inside the range -- at most the first and the
+// last one -- adds its elements one by one.
+//
+// VEC = dwords per load: 4 for bandwidth (8 bf16/fp16 or 4 fp32 elements per lane); 1 for
+// small messages on large groups, where the time is the launch plus the serial chain of
+// load round trips of one lane: one dword per buffer and lane spreads a 1 MB message over
+// 32 compute units instead of 1 and lets a lane keep 64 loads in flight, so p = 128 needs
+// two round trips.
 // ---------------------------------------------------------------------------
 
-template <bool ACCUM>
-__device__ __forceinline__ float rsa_element(const PtrTable& g, int p, size_t x, float before)
+template <int KIND> struct GradFormat {
+    static constexpr int kElemBytes = KIND == 2 ? 4 : 2;
+    static constexpr int kPerDword = KIND == 2 ? 1 : 2;
+};
+
+template <int KIND>
+__device__ __forceinline__ void widen_dword(float* out, uint32_t w)
 {
-    float partial = bf16_one(((const uint16_t*)g.ptr[0])[x]);
-    for (int q = 1; q < p; ++q) partial = partial + bf16_one(((const uint16_t*)g.ptr[q])[x]);
-    return (ACCUM ? before : 0.0f) + partial;
+    if constexpr (KIND == 0) {          // the bf16 bits are the upper half of the fp32 bits
+        out[0] = __uint_as_float(w << 16);
+        out[1] = __uint_as_float(w & 0xFFFF0000u);
+    } else if constexpr (KIND == 1) {
+        out[0] = (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xFFFFu));
+        out[1] = (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16));
+    } else {
+        out[0] = __uint_as_float(w);
+    }
 }
 
-// Partial sum over the p rank buffers of the 8 consecutive elements that start at element
-// `elem` (a multiple of 8 from 16-byte aligned bases), ranks in ascending order.  P > 0:
-// p = P known at compile time, all P loads issued before the first addition; P == 0: any p,
-// consumed in batches of 32 loads (a lane's additions are a serial chain, so the number of
-// load round trips per lane, p/32, is what a small message on a large group waits for: batches
-// of 8 put the floor of a p = 128 call at 25 us).
-template <int P, typename Tab>
-__device__ __forceinline__ void rsa_partial8(float (&s)[8], const Tab& g, int p, size_t elem)
+template <int KIND>
+__device__ __forceinline__ float widen_one(const void* buf, size_t x)
 {
-    if constexpr (P > 0) {
-        u32x4 v[P];
+    if constexpr (KIND == 0) return __uint_as_float((uint32_t)((const uint16_t*)buf)[x] << 16);
+    else if constexpr (KIND == 1) return (float)((const _Float16*)buf)[x];
+    else return ((const float*)buf)[x];
+}
+
+template <int KIND, int VEC> struct GradVec;      // the registers of one load
+template <int KIND> struct GradVec<KIND, 4> {
+    u32x4 v;
+    __device__ __forceinline__ void load(const void* base, size_t elem)
+    {
+        const char* a = (const char*)base + elem * GradFormat<KIND>::kElemBytes;
+        if constexpr (KIND == 2) v = MICS_LD(kRsaNtl, (const u32x4_a4*)a);
+        else v = MICS_LD(kRsaNtl, (const u32x4_a2*)a);
+    }
+    __device__ __forceinline__ uint32_t dword(int d) const { return v[d]; }
+};
+template <int KIND> struct GradVec<KIND, 1> {
+    uint32_t v;
+    __device__ __forceinline__ void load(const void* base, size_t elem)
+    {
+        const char* a = (const char*)base + elem * GradFormat<KIND>::kElemBytes;
+        if constexpr (KIND == 2) v = MICS_LD(kRsaNtl, (const uint32_t*)a);
+        else v = MICS_LD(kRsaNtl, (const u32_a2*)a);
+    }
+    __device__ __forceinline__ uint32_t dword(int) const { return v; }
+};
+
+template <int KIND, int VEC, bool FIRST>
+__device__ __forceinline__ void rsa_add(float* s, const GradVec<KIND, VEC>& v)
+{
+    constexpr int PD = GradFormat<KIND>::kPerDword;
+    #pragma unroll
+    for (int d = 0; d < VEC; ++d) {
+        float w[PD];
+        widen_dword<KIND>(w, v.dword(d));
         #pragma unroll
-        for (int q = 0; q < P; ++q)
-            v[q] = ld<kRsaNtl>((const u32x4*)((const uint16_t*)g.ptr[q] + elem));
-        #pragma unroll
-        for (int e = 0; e < 4; ++e) { s[2 * e] = bf16_lo(v[0][e]); s[2 * e + 1] = bf16_hi(v[0][e]); }
-        #pragma unroll
-        for (int q = 1; q < P; ++q) {
-            #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                s[2 * e] = s[2 * e] + bf16_lo(v[q][e]);
-                s[2 * e + 1] = s[2 * e + 1] + bf16_hi(v[q][e]);
-            }
-        }
-    } else {
-        constexpr int B = 32;
-        {
-            u32x4 first = ld<kRsaNtl>((const u32x4*)((const uint16_t*)g.ptr[0] + elem));
-            #pragma unroll
-            for (int e = 0; e < 4; ++e) { s[2 * e] = bf16_lo(first[e]); s[2 * e + 1] = bf16_hi(first[e]); }
-        }
-        for (int q0 = 1; q0 < p; q0 += B) {
-            u32x4 v[B];
-            #pragma unroll
-            for (int b = 0; b < B; ++b)
-                if (q0 + b < p) v[b] = ld<kRsaNtl>((const u32x4*)((const uint16_t*)g.ptr[q0 + b] + elem));
-            #pragma unroll
-            for (int b = 0; b < B; ++b) {
-                if (q0 + b < p) {
-                    #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        s[2 * e] = s[2 * e] + bf16_lo(v[b][e]);
-                        s[2 * e + 1] = s[2 * e + 1] + bf16_hi(v[b][e]);
-                    }
-                }
-            }
+        for (int e = 0; e < PD; ++e) {
+            if constexpr (FIRST) s[PD * d + e] = w[e];
+            else s[PD * d + e] = s[PD * d + e] + w[e];
         }
     }
 }
 
-// acc8 (16-byte aligned, 8 floats) = (ACCUM ? acc8 : +0) + partial sum at `elem`.
+// s = ((g_0 + g_1) + ...) + g_{p-1} for the lane's elements starting at virtual element `elem`.
+// P > 0: p = P at compile time; P == 0: any p.  The loads go out in batches of BATCH, every
+// batch entirely in flight before its first addition (P <= BATCH: all of them at once; a
+// batch of 32 128-bit loads would leave room for 3 wavefronts per SIMD only).
+template <int KIND, int VEC, int P, int BATCH, typename Tab>
+__device__ __forceinline__ void rsa_partial(float* s, const Tab& g, int p, size_t elem)
+{
+    if constexpr (P > 0) {
+        #pragma unroll
+        for (int q0 = 0; q0 < P; q0 += BATCH) {
+            GradVec<KIND, VEC> v[BATCH];
+            #pragma unroll
+            for (int b = 0; b < BATCH; ++b)
+                if (q0 + b < P) v[b].load(g.ptr[q0 + b], elem);
+            #pragma unroll
+            for (int b = 0; b < BATCH; ++b) {
+                if (q0 + b < P) {
+                    if (q0 + b == 0) rsa_add<KIND, VEC, true>(s, v[b]);
+                    else rsa_add<KIND, VEC, false>(s, v[b]);
+                }
+            }
+        }
+    } else {
+        {
+            GradVec<KIND, VEC> first;
+            first.load(g.ptr[0], elem);
+            rsa_add<KIND, VEC, true>(s, first);
+        }
+        for (int q0 = 1; q0 < p; q0 += BATCH) {
+            GradVec<KIND, VEC> v[BATCH];
+            #pragma unroll
+            for (int b = 0; b < BATCH; ++b)
+                if (q0 + b < p) v[b].load(g.ptr[q0 + b], elem);
+            #pragma unroll
+            for (int b = 0; b < BATCH; ++b)
+                if (q0 + b < p) rsa_add<KIND, VEC, false>(s, v[b]);
+        }
+    }
+}
+
+// acc_e[0 .. EPL) = (ACCUM ? acc_e : +0) + partial sum at virtual element `elem`.
 // SA ("stream the accumulator"): non-temporal accumulator loads and stores.  An accumulator
 // that fits the 256 MB Infinity Cache is best left cacheable -- its stores are absorbed there
 // and the next micro-step finds it again (plain/plain 6.3 TB/s, NT/NT 6.1 at S = 50 M) -- while
 // a larger one is best streamed past the caches (NT/NT 5.8 TB/s, plain/plain 5.4, and the
 // mixed NT-load/plain-store 5.1 at S = 200 M); the launcher picks by size.
-template <int P, bool ACCUM, bool SA, typename Tab>
-__device__ __forceinline__ void rsa_update8(float* __restrict__ acc8, const Tab& g, int p, size_t elem)
+template <int KIND, int VEC, int P, int BATCH, bool ACCUM, bool SA, typename Tab>
+__device__ __forceinline__ void rsa_update(float* __restrict__ acc_e, const Tab& g, int p, size_t elem)
 {
-    f32x4 a0 = {0.0f, 0.0f, 0.0f, 0.0f}, a1 = a0;
-    if (ACCUM) {   // issued before the gradient loads are consumed
-        a0 = ld<SA>((const f32x4*)acc8);
-        a1 = ld<SA>((const f32x4*)acc8 + 1);
-    }
-    float s[8];
-    rsa_partial8<P>(s, g, p, elem);
-    f32x4 o0 = {a0.x + s[0], a0.y + s[1], a0.z + s[2], a0.w + s[3]};
-    f32x4 o1 = {a1.x + s[4], a1.y + s[5], a1.z + s[6], a1.w + s[7]};
-    st<SA>((f32x4*)acc8, o0);
-    st<SA>((f32x4*)acc8 + 1, o1);
+    constexpr int EPL = VEC * GradFormat<KIND>::kPerDword;
+    float a[EPL];
+    #pragma unroll
+    for (int e = 0; e < EPL; ++e) a[e] = 0.0f;
+    if (ACCUM) ld_f32<EPL, SA>(a, acc_e);          // issued before the gradient loads are consumed
+    float s[EPL];
+    rsa_partial<KIND, VEC, P, BATCH>(s, g, p, elem);
+    #pragma unroll
+    for (int e = 0; e < EPL; ++e) a[e] = a[e] + s[e];
+    st_f32<EPL, SA>(acc_e, a);
 }
 
-template <int P, bool ACCUM, bool SA>
-__global__ __launch_bounds__(kRsaBlock) void rsa_vec_kernel(
-    float* __restrict__ acc, SmallTable<P> g, size_t nvec)
+template <int KIND, bool ACCUM, typename Tab>
+__device__ __forceinline__ void rsa_element(float* acc_e, const Tab& g, int p, size_t elem)
 {
-    const size_t stride = (size_t)gridDim.x * kRsaBlock;
-    for (size_t i = (size_t)blockIdx.x * kRsaBlock + threadIdx.x; i < nvec; i += stride)
-        rsa_update8<P, ACCUM, SA>(acc + 8 * i, g, P, 8 * i);
+    float partial = widen_one<KIND>(g.ptr[0], elem);
+    for (int q = 1; q < p; ++q) partial = partial + widen_one<KIND>(g.ptr[q], elem);
+    *acc_e = (ACCUM ? *acc_e : 0.0f) + partial;
 }
 
-// Any p.
-template <bool ACCUM, bool SA>
-__global__ __launch_bounds__(kRsaBlock) void rsa_vec_anyp_kernel(
-    float* __restrict__ acc, PtrTable g, int p, size_t nvec)
+// The lane's virtual elements [v0, v0 + EPL) against the call's range [lead, end): acc_v is
+// the accumulator address of virtual element 0 (never dereferenced outside the range).
+template <int KIND, int VEC, int P, int BATCH, bool ACCUM, bool SA, typename Tab>
+__device__ __forceinline__ void rsa_lane(float* acc, const Tab& g, int p, size_t v0, size_t lead, size_t end)
 {
-    const size_t stride = (size_t)gridDim.x * kRsaBlock;
-    for (size_t i = (size_t)blockIdx.x * kRsaBlock + threadIdx.x; i < nvec; i += stride)
-        rsa_update8<0, ACCUM, SA>(acc + 8 * i, g, p, 8 * i);
-}
-
-// Rank buffers that all start at the same non-zero offset `phase` (even, 2..14 bytes) inside
-// their 16-byte lines -- what an odd shard size gives: rank g's slice of every buffer starts
-// at g*S elements -- while the accumulator is aligned.  A lane rebuilds its 8 elements of each
-// buffer from the two aligned vectors that hold them (funnel shift by the uniform phase); the
-// second load of a lane is the first load of its neighbour, so memory traffic does not grow.
-// g.ptr[q] is the buffer address rounded DOWN to 16 bytes; vectors [v_begin, v_end) are done
-// here, and the launcher keeps v_begin >= 1 and v_end <= nvec - 1 so that both aligned loads
-// stay inside the caller's buffers (the first and last 8 elements go the element-wise way).
-__device__ __forceinline__ u32x4 funnel16(u32x4 lo, u32x4 hi, unsigned phase)
-{
-    uint32_t w0 = lo.x, w1 = lo.y, w2 = lo.z, w3 = lo.w, w4 = hi.x, w5 = hi.y, w6 = hi.z, w7 = hi.w;
-    if (phase & 4) { w0 = w1; w1 = w2; w2 = w3; w3 = w4; w4 = w5; w5 = w6; w6 = w7; }
-    if (phase & 8) { w0 = w2; w1 = w3; w2 = w4; w3 = w5; w4 = w6; }
-    u32x4 out = {w0, w1, w2, w3};
-    if (phase & 2) {
-        out.x = (w0 >> 16) | (w1 << 16);
-        out.y = (w1 >> 16) | (w2 << 16);
-        out.z = (w2 >> 16) | (w3 << 16);
-        out.w = (w3 >> 16) | (w4 << 16);
-    }
-    return out;
-}
-
-template <int P, bool ACCUM, bool SA, typename Tab>
-__global__ __launch_bounds__(kRsaBlock) void rsa_shift_kernel(
-    float* __restrict__ acc, Tab g, int p, unsigned phase, size_t v_begin, size_t v_end)
-{
-    const size_t stride = (size_t)gridDim.x * kRsaBlock;
-    for (size_t i = v_begin + (size_t)blockIdx.x * kRsaBlock + threadIdx.x; i < v_end; i += stride) {
-        f32x4 a0 = {0.0f, 0.0f, 0.0f, 0.0f}, a1 = a0;
-        if (ACCUM) {
-            a0 = ld<SA>((const f32x4*)acc + 2 * i);
-            a1 = ld<SA>((const f32x4*)acc + 2 * i + 1);
-        }
-        float s[8];
-        constexpr int B = P > 0 ? P : 16;
-        for (int q0 = 0; q0 < p; q0 += B) {
-            u32x4 lo[B], hi[B];
-            #pragma unroll
-            for (int b = 0; b < B; ++b) {
-                if (q0 + b < p) {
-                    lo[b] = ((const u32x4*)g.ptr[q0 + b])[i];
-                    hi[b] = ((const u32x4*)g.ptr[q0 + b])[i + 1];
-                }
-            }
-            #pragma unroll
-            for (int b = 0; b < B; ++b) {
-                if (q0 + b < p) {
-                    const u32x4 v = funnel16(lo[b], hi[b], phase);
-                    if (q0 + b == 0) {
-                        #pragma unroll
-                        for (int e = 0; e < 4; ++e) { s[2 * e] = bf16_lo(v[e]); s[2 * e + 1] = bf16_hi(v[e]); }
-                    } else {
-                        #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            s[2 * e] = s[2 * e] + bf16_lo(v[e]);
-                            s[2 * e + 1] = s[2 * e + 1] + bf16_hi(v[e]);
-                        }
-                    }
-                }
-            }
-        }
-        f32x4 o0 = {a0.x + s[0], a0.y + s[1], a0.z + s[2], a0.w + s[3]};
-        f32x4 o1 = {a1.x + s[4], a1.y + s[5], a1.z + s[6], a1.w + s[7]};
-        st<SA>((f32x4*)acc + 2 * i, o0);
-        st<SA>((f32x4*)acc + 2 * i + 1, o1);
+    constexpr size_t EPL = VEC * GradFormat<KIND>::kPerDword;
+    if (v0 >= lead && v0 + EPL <= end) {
+        rsa_update<KIND, VEC, P, BATCH, ACCUM, SA>(acc + (v0 - lead), g, p, v0);
+    } else {
+        const size_t lo = v0 > lead ? v0 : lead, hi = v0 + EPL < end ? v0 + EPL : end;
+        for (size_t e = lo; e < hi; ++e) rsa_element<KIND, ACCUM>(acc + (e - lead), g, p, e);
     }
 }
 
-// Coalesced form (many separately sharded tensors in one launch): workgroup x works on tile
-// x - tile_begin[t] of segment t; a lane owns 8 consecutive elements of the segment, the last
-// lane of a segment finishes a ragged end element by element.
+template <int KIND, int VEC, int P, bool ACCUM, bool SA, typename Tab>
+__global__ __launch_bounds__(VEC == 4 ? kRsaBlock : kNarrowBlock) void rsa_kernel(
+    float* __restrict__ acc, Tab g, int p, unsigned lead, size_t count)
+{
+    constexpr int BLOCK = VEC == 4 ? kRsaBlock : kNarrowBlock;
+    constexpr int BATCH = VEC == 4 ? MICS_RSA_BATCH : MICS_NARROW_BATCH;
+    constexpr size_t EPL = VEC * GradFormat<KIND>::kPerDword;
+    const size_t end = (size_t)lead + count;
+    const size_t nlanes = (end + EPL - 1) / EPL;
+    const size_t stride = (size_t)gridDim.x * BLOCK;
+    for (size_t i = (size_t)blockIdx.x * BLOCK + threadIdx.x; i < nlanes; i += stride)
+        rsa_lane<KIND, VEC, P, BATCH, ACCUM, SA>(acc, g, p, i * EPL, lead, end);
+}
+
+// Coalesced form (many separately sharded tensors in one launch, bf16): workgroup x works on
+// tile x - tile_begin[t] of segment t.  Every segment has its own virtual index space as in
+// rsa_kernel: src0 = position of its virtual element 0 in the rank buffers (a multiple of 2
+// elements from the 4-byte aligned base), [lead, end) = its elements, dst = accumulator
+// index of virtual element `lead`.
 struct ReduceSeg {
-    unsigned long long count, src_off, dst_off;   // elements
+    unsigned long long end, src0, dst;
+    unsigned lead, pad;
 };
 struct ReduceSegTable {
     int n;
@@ -517,178 +606,80 @@ __global__ __launch_bounds__(kRsaBlock) void rsa_seg_kernel(
 {
     const unsigned x = blockIdx.x;
     const int t = segment_of(tab.tile_begin, x);
-    const size_t count = tab.seg[t].count, src = tab.seg[t].src_off, dst = tab.seg[t].dst_off;
-    const size_t e0 = ((size_t)(x - tab.tile_begin[t]) * kRsaBlock + threadIdx.x) * 8;
-    if (e0 >= count) return;
-    if (e0 + 8 <= count) {
-        rsa_update8<P, ACCUM, SA>(acc + dst + e0, g, p, src + e0);
+    const size_t end = tab.seg[t].end, lead = tab.seg[t].lead;
+    const size_t v0 = ((size_t)(x - tab.tile_begin[t]) * kRsaBlock + threadIdx.x) * 8;
+    if (v0 >= end) return;
+    // the segment's virtual element e sits at element src0 + e of every rank buffer
+    const size_t src0 = tab.seg[t].src0;
+    float* acc_t = acc + tab.seg[t].dst;
+    if (v0 >= lead && v0 + 8 <= end) {
+        rsa_update<0, 4, P, MICS_RSA_BATCH, ACCUM, SA>(acc_t + (v0 - lead), g, p, src0 + v0);
     } else {
-        for (size_t e = e0; e < count; ++e) {
-            float partial = bf16_one(((const uint16_t*)g.ptr[0])[src + e]);
-            for (int q = 1; q < p; ++q) partial = partial + bf16_one(((const uint16_t*)g.ptr[q])[src + e]);
-            acc[dst + e] = (ACCUM ? acc[dst + e] : 0.0f) + partial;
-        }
+        const size_t lo = v0 > lead ? v0 : lead, hi = v0 + 8 < end ? v0 + 8 : end;
+        for (size_t e = lo; e < hi; ++e) rsa_element<0, ACCUM>(acc_t + (e - lead), g, p, src0 + e);
     }
-}
-
-// Gradients stored as IEEE binary16 (KIND 1: what mixed precision means on GPUs without bf16)
-// or binary32 (KIND 2: plain float32 training).  Same reduction, same order; widening is exact.
-// A lane owns one 128-bit vector per rank buffer: 8 binary16 or 4 binary32 elements.
-
-template <int KIND>
-__device__ __forceinline__ void widen_vec(float (&out)[8], u32x4 v)
-{
-    if constexpr (KIND == 1) {
-        #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const uint32_t pair = v[e];
-            out[2 * e] = (float)__builtin_bit_cast(_Float16, (uint16_t)(pair & 0xFFFFu));
-            out[2 * e + 1] = (float)__builtin_bit_cast(_Float16, (uint16_t)(pair >> 16));
-        }
-    } else {
-        #pragma unroll
-        for (int e = 0; e < 4; ++e) out[e] = __uint_as_float(v[e]);
-    }
-}
-
-template <int KIND>
-__device__ __forceinline__ float widen_one(const void* buf, size_t x)
-{
-    if constexpr (KIND == 1) return (float)((const _Float16*)buf)[x];
-    else return ((const float*)buf)[x];
-}
-
-template <int KIND, int P, bool ACCUM, bool SA, typename Tab>
-__global__ __launch_bounds__(kRsaBlock) void rsa_typed_vec_kernel(
-    float* __restrict__ acc, Tab g, int p, size_t nvec)
-{
-    constexpr int EPV = KIND == 1 ? 8 : 4;     // elements per 128-bit vector
-    const size_t stride = (size_t)gridDim.x * kRsaBlock;
-    for (size_t i = (size_t)blockIdx.x * kRsaBlock + threadIdx.x; i < nvec; i += stride) {
-        float a[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
-        if (ACCUM) {
-            #pragma unroll
-            for (int h = 0; h < EPV / 4; ++h) {
-                const f32x4 t = ld<SA>((const f32x4*)acc + (EPV / 4) * i + h);
-                a[4 * h] = t.x; a[4 * h + 1] = t.y; a[4 * h + 2] = t.z; a[4 * h + 3] = t.w;
-            }
-        }
-        float s[8], w[8];
-        if constexpr (P > 0) {
-            u32x4 v[P];
-            #pragma unroll
-            for (int q = 0; q < P; ++q) v[q] = ld<kRsaNtl>((const u32x4*)g.ptr[q] + i);
-            widen_vec<KIND>(s, v[0]);
-            #pragma unroll
-            for (int q = 1; q < P; ++q) {
-                widen_vec<KIND>(w, v[q]);
-                #pragma unroll
-                for (int e = 0; e < EPV; ++e) s[e] = s[e] + w[e];
-            }
-        } else {
-            constexpr int B = 32;
-            widen_vec<KIND>(s, ld<kRsaNtl>((const u32x4*)g.ptr[0] + i));
-            for (int q0 = 1; q0 < p; q0 += B) {
-                u32x4 v[B];
-                #pragma unroll
-                for (int b = 0; b < B; ++b)
-                    if (q0 + b < p) v[b] = ld<kRsaNtl>((const u32x4*)g.ptr[q0 + b] + i);
-                #pragma unroll
-                for (int b = 0; b < B; ++b) {
-                    if (q0 + b < p) {
-                        widen_vec<KIND>(w, v[b]);
-                        #pragma unroll
-                        for (int e = 0; e < EPV; ++e) s[e] = s[e] + w[e];
-                    }
-                }
-            }
-        }
-        #pragma unroll
-        for (int h = 0; h < EPV / 4; ++h) {
-            const f32x4 o = {a[4 * h] + s[4 * h], a[4 * h + 1] + s[4 * h + 1], a[4 * h + 2] + s[4 * h + 2],
-                             a[4 * h + 3] + s[4 * h + 3]};
-            st<SA>((f32x4*)acc + (EPV / 4) * i + h, o);
-        }
-    }
-}
-
-template <int KIND, bool ACCUM>
-__global__ __launch_bounds__(kBlock) void rsa_typed_scalar_kernel(
-    float* __restrict__ acc, PtrTable g, int p, size_t first, size_t count)
-{
-    const size_t stride = (size_t)gridDim.x * kBlock;
-    for (size_t x = first + (size_t)blockIdx.x * kBlock + threadIdx.x; x < count; x += stride) {
-        float partial = widen_one<KIND>(g.ptr[0], x);
-        for (int q = 1; q < p; ++q) partial = partial + widen_one<KIND>(g.ptr[q], x);
-        acc[x] = (ACCUM ? acc[x] : 0.0f) + partial;
-    }
-}
-
-// One element per lane: the tail of the vector kernels (elements [first, count))
-// and the whole range when some buffer is not 16-byte aligned.
-template <bool ACCUM>
-__global__ __launch_bounds__(kBlock) void rsa_scalar_kernel(
-    float* __restrict__ acc, PtrTable g, int p, size_t first, size_t count)
-{
-    const size_t stride = (size_t)gridDim.x * kBlock;
-    for (size_t x = first + (size_t)blockIdx.x * kBlock + threadIdx.x; x < count; x += stride)
-        acc[x] = rsa_element<ACCUM>(g, p, x, ACCUM ? acc[x] : 0.0f);
 }
 
 // ---------------------------------------------------------------------------
 // Step 2b: reduction of the replication-group all-reduce at the accumulation
 // boundary and the scaling to a mean (Section 3.4).  One lane owns 4 elements
-// per copy and pass.  `out` may be copies[0]: a lane reads its elements of every copy
-// before it writes them, and no other lane touches them.
+// per copy and pass (the last lane fewer, one by one).  `out` may be copies[0]: a lane
+// reads its elements of every copy before it writes them, and no other lane touches them.
 // ---------------------------------------------------------------------------
 
-// SO ("stream the output"): non-temporal stores for results too large for the Infinity Cache,
-// as for the accumulator of the reduce kernels.
-template <int R, bool SO>
-__global__ __launch_bounds__(kAvgBlock) void avg_vec_kernel(
-    float* out, SmallTable<R> a, float scale, size_t nvec)
+// s = ((a_0 + a_1) + ...) + a_{r-1} for the 4 elements from x.  R > 0: r = R at compile time,
+// all loads in flight at once; R == 0: any r in batches of 16 loads.
+template <int R, bool NT, typename Tab>
+__device__ __forceinline__ f32x4 avg_sum4(const Tab& a, int r, size_t x)
 {
-    const size_t stride = (size_t)gridDim.x * kAvgBlock;
-    for (size_t i = (size_t)blockIdx.x * kAvgBlock + threadIdx.x; i < nvec; i += stride) {
+    if constexpr (R > 0) {
         f32x4 v[R];
         #pragma unroll
-        for (int c = 0; c < R; ++c) v[c] = ld<kAvgNtl>((const f32x4*)a.ptr[c] + i);
-        f32x4 sv = v[0];
+        for (int c = 0; c < R; ++c) v[c] = MICS_LD(NT, (const f32x4_a4*)((const float*)a.ptr[c] + x));
+        f32x4 sum = v[0];
         #pragma unroll
-        for (int c = 1; c < R; ++c) sv = sv + v[c];
-        st<SO>((f32x4*)out + i, sv * scale);
-    }
-}
-
-template <bool SO>
-__global__ __launch_bounds__(kAvgBlock) void avg_vec_anyr_kernel(
-    float* out, PtrTable a, int r, float scale, size_t nvec)
-{
-    constexpr int B = 8;
-    const size_t stride = (size_t)gridDim.x * kAvgBlock;
-    for (size_t i = (size_t)blockIdx.x * kAvgBlock + threadIdx.x; i < nvec; i += stride) {
-        f32x4 sum = ld<kAvgNtl>((const f32x4*)a.ptr[0] + i);
+        for (int c = 1; c < R; ++c) sum = sum + v[c];
+        return sum;
+    } else {
+        constexpr int B = 16;
+        f32x4 sum = MICS_LD(NT, (const f32x4_a4*)((const float*)a.ptr[0] + x));
         for (int c0 = 1; c0 < r; c0 += B) {
             f32x4 v[B];
             #pragma unroll
             for (int b = 0; b < B; ++b)
-                if (c0 + b < r) v[b] = ld<kAvgNtl>((const f32x4*)a.ptr[c0 + b] + i);
+                if (c0 + b < r) v[b] = MICS_LD(NT, (const f32x4_a4*)((const float*)a.ptr[c0 + b] + x));
             #pragma unroll
             for (int b = 0; b < B; ++b)
                 if (c0 + b < r) sum = sum + v[b];
         }
-        st<SO>((f32x4*)out + i, sum * scale);
+        return sum;
     }
 }
 
-__global__ __launch_bounds__(kBlock) void avg_scalar_kernel(
-    float* out, PtrTable a, int r, float scale, size_t first, size_t count)
+template <typename Tab>
+__device__ __forceinline__ float avg_sum1(const Tab& a, int r, size_t x)
 {
-    const size_t stride = (size_t)gridDim.x * kBlock;
-    for (size_t x = first + (size_t)blockIdx.x * kBlock + threadIdx.x; x < count; x += stride) {
-        float sum = ((const float*)a.ptr[0])[x];
-        for (int c = 1; c < r; ++c) sum = sum + ((const float*)a.ptr[c])[x];
-        out[x] = sum * scale;
+    float sum = ((const float*)a.ptr[0])[x];
+    for (int c = 1; c < r; ++c) sum = sum + ((const float*)a.ptr[c])[x];
+    return sum;
+}
+
+// SO ("stream the output"): non-temporal stores for results too large for the Infinity Cache,
+// as for the accumulator of the reduce kernels.
+template <int R, bool SO, typename Tab>
+__global__ __launch_bounds__(kAvgBlock) void avg_kernel(
+    float* out, Tab a, int r, float scale, size_t count)
+{
+    const size_t nlanes = (count + 3) / 4;
+    const size_t stride = (size_t)gridDim.x * kAvgBlock;
+    for (size_t i = (size_t)blockIdx.x * kAvgBlock + threadIdx.x; i < nlanes; i += stride) {
+        const size_t x = 4 * i;
+        if (x + 4 <= count) {
+            const f32x4 sum = avg_sum4<R, kAvgNtl>(a, r, x);
+            MICS_ST(SO, (f32x4_a4*)(out + x), sum * scale);
+        } else {
+            for (size_t e = x; e < count; ++e) out[e] = avg_sum1(a, r, e) * scale;
+        }
     }
 }
 
@@ -720,120 +711,89 @@ __device__ __forceinline__ void adam_element(float& w, float& m, float& v, float
     v = v_new;
 }
 
+// The update of 4 consecutive elements from x given their gradient, states in place.
+template <bool BF16>
+__device__ __forceinline__ void adam_update4(float* master, float* exp_avg, float* exp_avg_sq,
+                                             uint16_t* param_bf16, size_t x, f32x4 g, f32x4 w, f32x4 m,
+                                             f32x4 v, const AdamScalars& hp)
+{
+    #pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        float we = w[e], me = m[e], ve = v[e];
+        adam_element(we, me, ve, g[e], hp);
+        w[e] = we; m[e] = me; v[e] = ve;
+    }
+    MICS_ST(kAdamNts, (f32x4_a4*)(master + x), w);
+    MICS_ST(kAdamNts, (f32x4_a4*)(exp_avg + x), m);
+    MICS_ST(kAdamNts, (f32x4_a4*)(exp_avg_sq + x), v);
+    if (BF16) {
+        u32x2 b = {bf16_pack(w.x, w.y), bf16_pack(w.z, w.w)};
+        MICS_ST(kAdamNts, (u32x2_a2*)(param_bf16 + x), b);
+    }
+}
+
+template <bool BF16>
+__device__ __forceinline__ void adam_update1(float* master, float* exp_avg, float* exp_avg_sq,
+                                             uint16_t* param_bf16, size_t x, float g, const AdamScalars& hp)
+{
+    float w = master[x], m = exp_avg[x], v = exp_avg_sq[x];
+    adam_element(w, m, v, g, hp);
+    master[x] = w; exp_avg[x] = m; exp_avg_sq[x] = v;
+    if (BF16) param_bf16[x] = bf16_single(w);
+}
+
 // One lane owns 4 consecutive elements per pass, so that every load and store instruction of
 // a wavefront covers one contiguous kilobyte (stores that leave gaps between lanes reach
 // memory as partial lines and cost extra traffic).  Four 128-bit loads are in flight before
-// the first use; the bf16 parameters leave as one 64-bit store.
+// the first use; the bf16 parameters leave as one 64-bit store.  The bf16 output may sit
+// anywhere on an element boundary -- for instance inside the stage-1 buffer of the next
+// parameter gather, at T_l + j*S.
 template <bool BF16>
-__global__ __launch_bounds__(kAdamBlock) void adam_vec_kernel(
+__global__ __launch_bounds__(kAdamBlock) void adam_kernel(
     float* __restrict__ master, float* __restrict__ exp_avg, float* __restrict__ exp_avg_sq,
-    uint16_t* __restrict__ param_bf16, const float* __restrict__ grad, size_t nvec, AdamScalars hp)
+    uint16_t* __restrict__ param_bf16, const float* __restrict__ grad, size_t count, AdamScalars hp)
 {
+    const size_t nlanes = (count + 3) / 4;
     const size_t stride = (size_t)gridDim.x * kAdamBlock;
-    for (size_t i = (size_t)blockIdx.x * kAdamBlock + threadIdx.x; i < nvec; i += stride) {
-        f32x4 g = ld<kAdamNtl>((const f32x4*)grad + i);
-        f32x4 w = ld<kAdamNtl>((const f32x4*)master + i);
-        f32x4 m = ld<kAdamNtl>((const f32x4*)exp_avg + i);
-        f32x4 v = ld<kAdamNtl>((const f32x4*)exp_avg_sq + i);
-        #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            float we = w[e], me = m[e], ve = v[e];
-            adam_element(we, me, ve, g[e], hp);
-            w[e] = we; m[e] = me; v[e] = ve;
-        }
-        st<kAdamNts>((f32x4*)master + i, w);
-        st<kAdamNts>((f32x4*)exp_avg + i, m);
-        st<kAdamNts>((f32x4*)exp_avg_sq + i, v);
-        if (BF16) {
-            u32x2 b = {bf16_pack(w.x, w.y), bf16_pack(w.z, w.w)};
-            st<kAdamNts>((u32x2*)param_bf16 + i, b);
+    for (size_t i = (size_t)blockIdx.x * kAdamBlock + threadIdx.x; i < nlanes; i += stride) {
+        const size_t x = 4 * i;
+        if (x + 4 <= count) {
+            const f32x4 g = MICS_LD(kAdamNtl, (const f32x4_a4*)(grad + x));
+            const f32x4 w = MICS_LD(kAdamNtl, (const f32x4_a4*)(master + x));
+            const f32x4 m = MICS_LD(kAdamNtl, (const f32x4_a4*)(exp_avg + x));
+            const f32x4 v = MICS_LD(kAdamNtl, (const f32x4_a4*)(exp_avg_sq + x));
+            adam_update4<BF16>(master, exp_avg, exp_avg_sq, param_bf16, x, g, w, m, v, hp);
+        } else {
+            for (size_t e = x; e < count; ++e)
+                adam_update1<BF16>(master, exp_avg, exp_avg_sq, param_bf16, e, grad[e], hp);
         }
     }
 }
 
 // Replica average fused into the Adam step: the averaged gradient of a lane's 4 elements is
 // formed in registers from the r accumulator copies (same additions, same order, same multiply
-// as avg_vec_kernel) and goes straight into adam_element, so it is neither written nor re-read:
+// as avg_kernel) and goes straight into adam_element, so it is neither written nor re-read:
 // 4r + 12 bytes read and 14 written per element instead of (4r + 4) + 30.  R > 0: r = R at
-// compile time; R == 0: any r in batches of 8 loads.
+// compile time; R == 0: any r in batches of 16 loads.
 template <int R, bool BF16, typename Tab>
-__global__ __launch_bounds__(kAdamBlock) void avg_adam_vec_kernel(
+__global__ __launch_bounds__(kFusedBlock) void avg_adam_kernel(
     float* __restrict__ master, float* __restrict__ exp_avg, float* __restrict__ exp_avg_sq,
-    uint16_t* __restrict__ param_bf16, Tab a, int r, float scale, size_t nvec, AdamScalars hp)
+    uint16_t* __restrict__ param_bf16, Tab a, int r, float scale, size_t count, AdamScalars hp)
 {
-    const size_t stride = (size_t)gridDim.x * kAdamBlock;
-    for (size_t i = (size_t)blockIdx.x * kAdamBlock + threadIdx.x; i < nvec; i += stride) {
-        f32x4 w = ld<kAdamNtl>((const f32x4*)master + i);
-        f32x4 m = ld<kAdamNtl>((const f32x4*)exp_avg + i);
-        f32x4 v = ld<kAdamNtl>((const f32x4*)exp_avg_sq + i);
-        f32x4 sum;
-        if constexpr (R > 0) {
-            f32x4 c[R];
-            #pragma unroll
-            for (int q = 0; q < R; ++q) c[q] = ld<kAdamNtl>((const f32x4*)a.ptr[q] + i);
-            sum = c[0];
-            #pragma unroll
-            for (int q = 1; q < R; ++q) sum = sum + c[q];
+    const size_t nlanes = (count + 3) / 4;
+    const size_t stride = (size_t)gridDim.x * kFusedBlock;
+    for (size_t i = (size_t)blockIdx.x * kFusedBlock + threadIdx.x; i < nlanes; i += stride) {
+        const size_t x = 4 * i;
+        if (x + 4 <= count) {
+            const f32x4 w = MICS_LD(kAdamNtl, (const f32x4_a4*)(master + x));
+            const f32x4 m = MICS_LD(kAdamNtl, (const f32x4_a4*)(exp_avg + x));
+            const f32x4 v = MICS_LD(kAdamNtl, (const f32x4_a4*)(exp_avg_sq + x));
+            const f32x4 sum = avg_sum4<R, kAdamNtl>(a, r, x);
+            adam_update4<BF16>(master, exp_avg, exp_avg_sq, param_bf16, x, sum * scale, w, m, v, hp);
         } else {
-            constexpr int B = 8;
-            sum = ld<kAdamNtl>((const f32x4*)a.ptr[0] + i);
-            for (int q0 = 1; q0 < r; q0 += B) {
-                f32x4 c[B];
-                #pragma unroll
-                for (int b = 0; b < B; ++b)
-                    if (q0 + b < r) c[b] = ld<kAdamNtl>((const f32x4*)a.ptr[q0 + b] + i);
-                #pragma unroll
-                for (int b = 0; b < B; ++b)
-                    if (q0 + b < r) sum = sum + c[b];
-            }
+            for (size_t e = x; e < count; ++e)
+                adam_update1<BF16>(master, exp_avg, exp_avg_sq, param_bf16, e, avg_sum1(a, r, e) * scale, hp);
         }
-        const f32x4 g = sum * scale;
-        #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            float we = w[e], me = m[e], ve = v[e];
-            adam_element(we, me, ve, g[e], hp);
-            w[e] = we; m[e] = me; v[e] = ve;
-        }
-        st<kAdamNts>((f32x4*)master + i, w);
-        st<kAdamNts>((f32x4*)exp_avg + i, m);
-        st<kAdamNts>((f32x4*)exp_avg_sq + i, v);
-        if (BF16) {
-            u32x2 b = {bf16_pack(w.x, w.y), bf16_pack(w.z, w.w)};
-            st<kAdamNts>((u32x2*)param_bf16 + i, b);
-        }
-    }
-}
-
-template <bool BF16>
-__global__ __launch_bounds__(kBlock) void avg_adam_scalar_kernel(
-    float* __restrict__ master, float* __restrict__ exp_avg, float* __restrict__ exp_avg_sq,
-    uint16_t* __restrict__ param_bf16, PtrTable a, int r, float scale, size_t first, size_t count,
-    AdamScalars hp)
-{
-    const size_t stride = (size_t)gridDim.x * kBlock;
-    for (size_t x = first + (size_t)blockIdx.x * kBlock + threadIdx.x; x < count; x += stride) {
-        float sum = ((const float*)a.ptr[0])[x];
-        for (int c = 1; c < r; ++c) sum = sum + ((const float*)a.ptr[c])[x];
-        const float g = sum * scale;
-        float w = master[x], m = exp_avg[x], v = exp_avg_sq[x];
-        adam_element(w, m, v, g, hp);
-        master[x] = w; exp_avg[x] = m; exp_avg_sq[x] = v;
-        if (BF16) param_bf16[x] = bf16_single(w);
-    }
-}
-
-template <bool BF16>
-__global__ __launch_bounds__(kBlock) void adam_scalar_kernel(
-    float* __restrict__ master, float* __restrict__ exp_avg, float* __restrict__ exp_avg_sq,
-    uint16_t* __restrict__ param_bf16, const float* __restrict__ grad, size_t first, size_t count,
-    AdamScalars hp)
-{
-    const size_t stride = (size_t)gridDim.x * kBlock;
-    for (size_t x = first + (size_t)blockIdx.x * kBlock + threadIdx.x; x < count; x += stride) {
-        float w = master[x], m = exp_avg[x], v = exp_avg_sq[x];
-        adam_element(w, m, v, grad[x], hp);
-        master[x] = w; exp_avg[x] = m; exp_avg_sq[x] = v;
-        if (BF16) param_bf16[x] = bf16_single(w);
     }
 }
 
@@ -842,6 +802,12 @@ __global__ __launch_bounds__(kBlock) void adam_scalar_kernel(
 // ---------------------------------------------------------------------------
 
 std::atomic<int> g_blocks_per_cu{0};
+// Accumulators (reduce) and outputs (replica average) up to this size are left cacheable,
+// larger ones are streamed (see rsa_update).
+constexpr size_t kDefaultStreamBytes = 224u << 20;
+std::atomic<size_t> g_stream_bytes{kDefaultStreamBytes};
+
+inline bool stream_acc(size_t elements) { return elements * 4 > g_stream_bytes.load(); }
 
 int compute_units(int* out)
 {
@@ -875,24 +841,24 @@ int grid_for(size_t items, int block, int bpc, unsigned* blocks)
     return 0;
 }
 
-constexpr int kTailBpc = 8;
+template <typename T> struct same_type { typedef T type; };
 
-inline int launch_status()
+// Launches `kernel` and returns the launch call's own status: the caller's HIP error state
+// (an earlier, unrelated error of the thread) is neither reported nor cleared here.
+template <typename... KArgs>
+int launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t st,
+           typename same_type<KArgs>::type... args)
 {
-    hipError_t e = hipGetLastError();
-    return e == hipSuccess ? 0 : (int)e;
+    void* ptrs[] = {(void*)&args...};
+    return (int)hipLaunchKernel((const void*)kernel, grid, block, ptrs, 0, st);
 }
-
-// Accumulators up to this size are left cacheable, larger ones are streamed (see rsa_update8).
-constexpr size_t kAccCacheableBytes = 224u << 20;
-inline bool stream_acc(size_t elements) { return elements * 4 > kAccCacheableBytes; }
 
 // Calls f(std::bool_constant<a>, std::bool_constant<b>) for two runtime flags.
 template <typename F>
-void dispatch2(bool a, bool b, F&& f)
+int dispatch2(bool a, bool b, F&& f)
 {
-    if (a) { if (b) f(std::true_type{}, std::true_type{}); else f(std::true_type{}, std::false_type{}); }
-    else   { if (b) f(std::false_type{}, std::true_type{}); else f(std::false_type{}, std::false_type{}); }
+    if (a) return b ? f(std::true_type{}, std::true_type{}) : f(std::true_type{}, std::false_type{});
+    return b ? f(std::false_type{}, std::true_type{}) : f(std::false_type{}, std::false_type{});
 }
 
 template <int N>
@@ -903,29 +869,26 @@ SmallTable<N> small(const PtrTable& t)
     return s;
 }
 
-template <int P>
-void rsa_launch_fixed(float* acc, const PtrTable& g, size_t nvec, bool accumulate, unsigned blocks,
-                      hipStream_t st)
+// Calls f(std::integral_constant<int, P>) with P = p if p has an unrolled kernel, else P = 0.
+template <typename F>
+int dispatch_group(int p, F&& f)
 {
-    dispatch2(accumulate, stream_acc(nvec * 8), [&](auto A, auto SA) {
-        hipLaunchKernelGGL((rsa_vec_kernel<P, A.value, SA.value>), dim3(blocks), dim3(kRsaBlock), 0, st, acc,
-                           small<P>(g), nvec);
-    });
-}
-
-template <int R>
-void avg_launch_fixed(float* out, const PtrTable& a, float scale, size_t nvec, unsigned blocks,
-                      hipStream_t st)
-{
-    dispatch2(stream_acc(nvec * 4), false, [&](auto SO, auto) {
-        hipLaunchKernelGGL((avg_vec_kernel<R, SO.value>), dim3(blocks), dim3(kAvgBlock), 0, st, out,
-                           small<R>(a), scale, nvec);
-    });
+    switch (p) {
+        case 1: return f(std::integral_constant<int, 1>{});
+        case 2: return f(std::integral_constant<int, 2>{});
+        case 4: return f(std::integral_constant<int, 4>{});
+        case 8: return f(std::integral_constant<int, 8>{});
+        case 16: return f(std::integral_constant<int, 16>{});
+        case 32: return f(std::integral_constant<int, 32>{});
+        default: return f(std::integral_constant<int, 0>{});
+    }
 }
 
 }  // namespace
 
 void set_blocks_per_cu(int n) { g_blocks_per_cu.store(n); }
+
+void set_stream_threshold_bytes(size_t n) { g_stream_bytes.store(n ? n : kDefaultStreamBytes); }
 
 const char* hip_error_text(int err) { return hipGetErrorString((hipError_t)err); }
 
@@ -933,204 +896,177 @@ int launch_reorder(void* dst, const PtrTable& src, size_t n_valid_bytes, size_t 
                    int k, bool vec16, void* stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    unsigned total = 0;
     if (vec16) {
         // spread the block budget over the p chunks
+        unsigned total = 0;
         if (int e = grid_for(shard_bytes / 16 * (size_t)p, kReorderBlock, MICS_REORDER_BPC, &total)) return e;
         unsigned bx = (total + (unsigned)p - 1) / (unsigned)p;
-        hipLaunchKernelGGL(reorder_vec_kernel, dim3(bx, (unsigned)p), dim3(kReorderBlock), 0, st,
-                           (u32x4*)dst, src, shard_bytes / 16, n_valid_bytes, k);
-    } else {
-        size_t tiles = (shard_bytes + 15 + kTileBytes - 1) / kTileBytes + 1;
-        if (int e = grid_for(tiles * (size_t)p * kBlock, kBlock, MICS_REORDER_BPC, &total)) return e;
-        unsigned bx = (total + (unsigned)p - 1) / (unsigned)p;
-        if (bx > tiles) bx = (unsigned)tiles;
-        hipLaunchKernelGGL(reorder_lds_kernel, dim3(bx, (unsigned)p), dim3(kBlock), 0, st,
-                           (unsigned char*)dst, src, shard_bytes, n_valid_bytes, k);
+        return launch(reorder_vec_kernel, dim3(bx, (unsigned)p), dim3(kReorderBlock), st, (u32x4*)dst, src,
+                      shard_bytes / 16, n_valid_bytes, k);
     }
-    return launch_status();
+    const Segment one = {n_valid_bytes, shard_bytes, 0, 0};
+    return launch_reorder_coalesced(dst, src, &one, 1, p, k, 1, false, stream);
 }
 
 namespace {
-void rsa_scalar_launch(float* acc, const PtrTable& g, int p, size_t first, size_t end, bool accumulate,
-                       unsigned blocks, hipStream_t st)
+
+template <int KIND, int VEC, int P, bool ACCUM, bool SA>
+int rsa_launch(float* acc, const PtrTable& g, int p, unsigned lead, size_t count, unsigned blocks,
+               hipStream_t st)
 {
-    if (accumulate)
-        hipLaunchKernelGGL(rsa_scalar_kernel<true>, dim3(blocks), dim3(kBlock), 0, st, acc, g, p, first, end);
+    constexpr int BLOCK = VEC == 4 ? kRsaBlock : kNarrowBlock;
+    if constexpr (P > 0)
+        return launch(rsa_kernel<KIND, VEC, P, ACCUM, SA, SmallTable<P>>, dim3(blocks), dim3(BLOCK), st, acc,
+                      small<P>(g), p, lead, count);
     else
-        hipLaunchKernelGGL(rsa_scalar_kernel<false>, dim3(blocks), dim3(kBlock), 0, st, acc, g, p, first, end);
+        return launch(rsa_kernel<KIND, VEC, 0, ACCUM, SA, PtrTable>, dim3(blocks), dim3(BLOCK), st, acc, g, p,
+                      lead, count);
 }
+
+template <int KIND>
+int rsa_launch_kind(float* acc, const PtrTable& g, int p, unsigned lead, size_t count, bool accumulate,
+                    hipStream_t st)
+{
+    constexpr size_t PD = GradFormat<KIND>::kPerDword;
+    unsigned blocks = 0;
+    // small message on a large group: one dword per lane and buffer
+    if (p >= MICS_NARROW_MIN_P && count <= (size_t)MICS_NARROW_MAX_ELEMS / (size_t)p) {
+        const size_t nlanes = (lead + count + PD - 1) / PD;
+        if (int e = grid_for(nlanes, kNarrowBlock, MICS_RSA_BPC, &blocks)) return e;
+        return accumulate ? rsa_launch<KIND, 1, 0, true, false>(acc, g, p, lead, count, blocks, st)
+                          : rsa_launch<KIND, 1, 0, false, false>(acc, g, p, lead, count, blocks, st);
+    }
+    const size_t nlanes = (lead + count + 4 * PD - 1) / (4 * PD);
+    if (int e = grid_for(nlanes, kRsaBlock, MICS_RSA_BPC, &blocks)) return e;
+    return dispatch2(accumulate, stream_acc(count), [&](auto A, auto SA) {
+        if constexpr (KIND == 0) {
+            return dispatch_group(p, [&](auto P) {
+                return rsa_launch<KIND, 4, P.value, A.value, SA.value>(acc, g, p, lead, count, blocks, st);
+            });
+        } else {
+            switch (p) {
+                case 8: return rsa_launch<KIND, 4, 8, A.value, SA.value>(acc, g, p, lead, count, blocks, st);
+                case 16: return rsa_launch<KIND, 4, 16, A.value, SA.value>(acc, g, p, lead, count, blocks, st);
+                default: return rsa_launch<KIND, 4, 0, A.value, SA.value>(acc, g, p, lead, count, blocks, st);
+            }
+        }
+    });
+}
+
+// Rounds 2-byte element pointers down to 4 bytes when all of them sit at the same position
+// inside their dword; returns how many elements they moved back (the kernels' `lead`).
+unsigned align_gradient_pointers(PtrTable& g, int p, int elem_bytes)
+{
+    if (elem_bytes != 2) return 0;
+    const uintptr_t odd = (uintptr_t)g.ptr[0] & 2;
+    for (int q = 1; q < p; ++q)
+        if (((uintptr_t)g.ptr[q] & 2) != odd) return 0;    // mixed: 2-byte aligned loads (slower)
+    if (!odd) return 0;
+    for (int q = 0; q < p; ++q) g.ptr[q] = (const char*)g.ptr[q] - 2;
+    return 1;
+}
+
 }  // namespace
 
-// grad_phase: 0 = every buffer 16-byte aligned (with an aligned accumulator); 2..14 = every
-// gradient buffer starts that many bytes into a 16-byte line (accumulator aligned); -1 = no
-// common alignment: element-wise kernel.
-int launch_reduce_scatter_accum(float* acc, const PtrTable& g, size_t count, int p, bool accumulate,
-                                int grad_phase, void* stream)
+int launch_reduce_scatter_accum(float* acc, const PtrTable& grads, size_t count, int p, bool accumulate,
+                                int kind, void* stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    unsigned blocks = 0;
-    const size_t nvec_all = count / 8;
-    if (grad_phase > 0 && nvec_all >= 3) {
-        // middle vectors through the shift kernel, first and last 8 (+ tail) elements one by one
-        PtrTable down{};
-        for (int q = 0; q < p; ++q) down.ptr[q] = (const char*)g.ptr[q] - grad_phase;
-        const size_t v_begin = 1, v_end = nvec_all - 1;
-        if (int e = grid_for(v_end - v_begin, kRsaBlock, MICS_RSA_BPC, &blocks)) return e;
-        dispatch2(accumulate, stream_acc(count), [&](auto A, auto SA) {
-            if (p == 16)
-                hipLaunchKernelGGL((rsa_shift_kernel<16, A.value, SA.value, SmallTable<16>>), dim3(blocks),
-                                   dim3(kRsaBlock), 0, st, acc, small<16>(down), p, (unsigned)grad_phase,
-                                   v_begin, v_end);
-            else
-                hipLaunchKernelGGL((rsa_shift_kernel<0, A.value, SA.value, PtrTable>), dim3(blocks),
-                                   dim3(kRsaBlock), 0, st, acc, down, p, (unsigned)grad_phase, v_begin, v_end);
-        });
-        if (int e = launch_status()) return e;
-        if (int e = grid_for(8, kBlock, kTailBpc, &blocks)) return e;
-        rsa_scalar_launch(acc, g, p, 0, 8, accumulate, blocks, st);
-        if (int e = launch_status()) return e;
-        if (int e = grid_for(count - v_end * 8, kBlock, kTailBpc, &blocks)) return e;
-        rsa_scalar_launch(acc, g, p, v_end * 8, count, accumulate, blocks, st);
-        return launch_status();
+    PtrTable g = grads;
+    const unsigned lead = align_gradient_pointers(g, p, kind == 2 ? 4 : 2);
+    switch (kind) {
+        case 0: return rsa_launch_kind<0>(acc, g, p, lead, count, accumulate, st);
+        case 1: return rsa_launch_kind<1>(acc, g, p, lead, count, accumulate, st);
+        default: return rsa_launch_kind<2>(acc, g, p, lead, count, accumulate, st);
     }
-    const size_t nvec = grad_phase == 0 ? nvec_all : 0;
-    if (nvec) {
-        if (int e = grid_for(nvec, kRsaBlock, MICS_RSA_BPC, &blocks)) return e;
-        switch (p) {
-            case 1: rsa_launch_fixed<1>(acc, g, nvec, accumulate, blocks, st); break;
-            case 2: rsa_launch_fixed<2>(acc, g, nvec, accumulate, blocks, st); break;
-            case 4: rsa_launch_fixed<4>(acc, g, nvec, accumulate, blocks, st); break;
-            case 8: rsa_launch_fixed<8>(acc, g, nvec, accumulate, blocks, st); break;
-            case 16: rsa_launch_fixed<16>(acc, g, nvec, accumulate, blocks, st); break;
-            case 32: rsa_launch_fixed<32>(acc, g, nvec, accumulate, blocks, st); break;
-            default:
-                dispatch2(accumulate, stream_acc(count), [&](auto A, auto SA) {
-                    hipLaunchKernelGGL((rsa_vec_anyp_kernel<A.value, SA.value>), dim3(blocks),
-                                       dim3(kRsaBlock), 0, st, acc, g, p, nvec);
-                });
-        }
-        if (int e = launch_status()) return e;
-    }
-    const size_t first = nvec * 8;
-    if (first < count) {
-        if (int e = grid_for(count - first, kBlock, kTailBpc, &blocks)) return e;
-        rsa_scalar_launch(acc, g, p, first, count, accumulate, blocks, st);
-        if (int e = launch_status()) return e;
-    }
-    return 0;
 }
 
-int launch_replica_average(float* out, const PtrTable& a, size_t count, int r, float scale,
-                           bool vec16, void* stream)
+int launch_replica_average(float* out, const PtrTable& a, size_t count, int r, float scale, void* stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    const size_t nvec = vec16 ? count / 4 : 0;
     unsigned blocks = 0;
-    if (nvec) {
-        if (int e = grid_for(nvec, kAvgBlock, MICS_AVG_BPC, &blocks)) return e;
+    if (int e = grid_for((count + 3) / 4, kAvgBlock, MICS_AVG_BPC, &blocks)) return e;
+    return dispatch2(stream_acc(count), false, [&](auto SO, auto) {
         switch (r) {
-            case 1: avg_launch_fixed<1>(out, a, scale, nvec, blocks, st); break;
-            case 2: avg_launch_fixed<2>(out, a, scale, nvec, blocks, st); break;
-            case 4: avg_launch_fixed<4>(out, a, scale, nvec, blocks, st); break;
-            case 8: avg_launch_fixed<8>(out, a, scale, nvec, blocks, st); break;
-            default:
-                dispatch2(stream_acc(count), false, [&](auto SO, auto) {
-                    hipLaunchKernelGGL(avg_vec_anyr_kernel<SO.value>, dim3(blocks), dim3(kAvgBlock), 0, st,
-                                       out, a, r, scale, nvec);
-                });
+            case 1: return launch(avg_kernel<1, SO.value, SmallTable<1>>, dim3(blocks), dim3(kAvgBlock), st, out, small<1>(a), r, scale, count);
+            case 2: return launch(avg_kernel<2, SO.value, SmallTable<2>>, dim3(blocks), dim3(kAvgBlock), st, out, small<2>(a), r, scale, count);
+            case 4: return launch(avg_kernel<4, SO.value, SmallTable<4>>, dim3(blocks), dim3(kAvgBlock), st, out, small<4>(a), r, scale, count);
+            case 8: return launch(avg_kernel<8, SO.value, SmallTable<8>>, dim3(blocks), dim3(kAvgBlock), st, out, small<8>(a), r, scale, count);
+            default: return launch(avg_kernel<0, SO.value, PtrTable>, dim3(blocks), dim3(kAvgBlock), st, out, a, r, scale, count);
         }
-        if (int e = launch_status()) return e;
-    }
-    const size_t first = nvec * 4;
-    if (first < count) {
-        if (int e = grid_for(count - first, kBlock, kTailBpc, &blocks)) return e;
-        hipLaunchKernelGGL(avg_scalar_kernel, dim3(blocks), dim3(kBlock), 0, st, out, a, r, scale,
-                           first, count);
-        if (int e = launch_status()) return e;
-    }
-    return 0;
+    });
 }
 
 int launch_adam(float* master, float* exp_avg, float* exp_avg_sq, uint16_t* param_bf16,
-                const float* grad, size_t count, const AdamScalars& hp, bool vec16, void* stream)
+                const float* grad, size_t count, const AdamScalars& hp, void* stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    const size_t nvec = vec16 ? count / 4 : 0;
     unsigned blocks = 0;
-    if (nvec) {
-        if (int e = grid_for(nvec, kAdamBlock, MICS_ADAM_BPC, &blocks)) return e;
-        if (param_bf16)
-            hipLaunchKernelGGL(adam_vec_kernel<true>, dim3(blocks), dim3(kAdamBlock), 0, st, master,
-                               exp_avg, exp_avg_sq, param_bf16, grad, nvec, hp);
-        else
-            hipLaunchKernelGGL(adam_vec_kernel<false>, dim3(blocks), dim3(kAdamBlock), 0, st,
-                               master, exp_avg, exp_avg_sq, param_bf16, grad, nvec, hp);
-        if (int e = launch_status()) return e;
-    }
-    const size_t first = nvec * 4;
-    if (first < count) {
-        if (int e = grid_for(count - first, kBlock, kTailBpc, &blocks)) return e;
-        if (param_bf16)
-            hipLaunchKernelGGL(adam_scalar_kernel<true>, dim3(blocks), dim3(kBlock), 0, st, master,
-                               exp_avg, exp_avg_sq, param_bf16, grad, first, count, hp);
-        else
-            hipLaunchKernelGGL(adam_scalar_kernel<false>, dim3(blocks), dim3(kBlock), 0, st, master,
-                               exp_avg, exp_avg_sq, param_bf16, grad, first, count, hp);
-        if (int e = launch_status()) return e;
-    }
-    return 0;
+    if (int e = grid_for((count + 3) / 4, kAdamBlock, MICS_ADAM_BPC, &blocks)) return e;
+    if (param_bf16)
+        return launch(adam_kernel<true>, dim3(blocks), dim3(kAdamBlock), st, master, exp_avg, exp_avg_sq,
+                      param_bf16, grad, count, hp);
+    return launch(adam_kernel<false>, dim3(blocks), dim3(kAdamBlock), st, master, exp_avg, exp_avg_sq,
+                  param_bf16, grad, count, hp);
 }
 
 int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs, int n, int p, int k,
-                             int elem_bytes, void* stream)
+                             int elem_bytes, bool vec16, void* stream)
 {
     hipStream_t st = (hipStream_t)stream;
     const size_t eb = (size_t)elem_bytes;
     for (int first = 0; first < n; first += kMaxSeg) {
-        ReorderSegTable tab;
-        tab.n = n - first < kMaxSeg ? n - first : kMaxSeg;
+        const int nt = n - first < kMaxSeg ? n - first : kMaxSeg;
         size_t tiles = 0;
-        for (int t = 0; t < tab.n; ++t) {
-            const Segment& sg = segs[first + t];
-            tab.tile_begin[t] = (unsigned)tiles;
-            tab.seg[t].shard_vecs = sg.shard_elems * eb / 16;
-            tab.seg[t].valid_bytes = sg.numel * eb;
-            tab.seg[t].src_vec = sg.src_offset * eb / 16;
-            tab.seg[t].dst_vec = sg.dst_offset * eb / 16;
-            tiles += (tab.seg[t].shard_vecs + kSegTileVecs - 1) / kSegTileVecs;
-            if (tiles > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
+        if (vec16) {
+            ReorderSegTable tab;
+            tab.n = nt;
+            for (int t = 0; t < nt; ++t) {
+                const Segment& sg = segs[first + t];
+                tab.tile_begin[t] = (unsigned)tiles;
+                tab.seg[t].shard_vecs = sg.shard_elems * eb / 16;
+                tab.seg[t].valid_bytes = sg.numel * eb;
+                tab.seg[t].src_vec = sg.src_offset * eb / 16;
+                tab.seg[t].dst_vec = sg.dst_offset * eb / 16;
+                tiles += (tab.seg[t].shard_vecs + kSegTileVecs - 1) / kSegTileVecs;
+                if (tiles > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
+            }
+            for (int t = nt; t <= kMaxSeg; ++t) tab.tile_begin[t] = 0xFFFFFFFFu;
+            if (tiles == 0) continue;
+            if (int e = launch(reorder_seg_kernel, dim3((unsigned)tiles, (unsigned)p), dim3(kSegBlock), st,
+                               (u32x4*)dst, src, tab, k))
+                return e;
+        } else {
+            LdsSegTable tab;
+            tab.n = nt;
+            for (int t = 0; t < nt; ++t) {
+                const Segment& sg = segs[first + t];
+                tab.tile_begin[t] = (unsigned)tiles;
+                tab.seg[t].shard_bytes = sg.shard_elems * eb;
+                tab.seg[t].valid_bytes = sg.numel * eb;
+                tab.seg[t].src_byte = sg.src_offset * eb;
+                tab.seg[t].dst_byte = sg.dst_offset * eb;
+                // a chunk of shard_bytes that starts up to 15 bytes into the destination's 16-byte grid
+                if (sg.numel) tiles += (tab.seg[t].shard_bytes + 15 + kTileBytes - 1) / kTileBytes;
+                if (tiles > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
+            }
+            for (int t = nt; t <= kMaxSeg; ++t) tab.tile_begin[t] = 0xFFFFFFFFu;
+            if (tiles == 0) continue;
+            if (int e = launch(reorder_lds_kernel, dim3((unsigned)tiles, (unsigned)p), dim3(kBlock), st,
+                               (unsigned char*)dst, src, tab, k))
+                return e;
         }
-        for (int t = tab.n; t <= kMaxSeg; ++t) tab.tile_begin[t] = 0xFFFFFFFFu;
-        if (tiles == 0) continue;
-        hipLaunchKernelGGL(reorder_seg_kernel, dim3((unsigned)tiles, (unsigned)p), dim3(kSegBlock),
-                           0, st, (u32x4*)dst, src, tab, k);
-        if (int e = launch_status()) return e;
     }
     return 0;
 }
 
-namespace {
-template <int P>
-void rsa_seg_launch(float* acc, const PtrTable& g, int p, const ReduceSegTable& tab, unsigned tiles,
-                    bool accumulate, bool sa, hipStream_t st)
-{
-    dispatch2(accumulate, sa, [&](auto A, auto SA) {
-        if constexpr (P > 0)
-            hipLaunchKernelGGL((rsa_seg_kernel<P, A.value, SA.value, SmallTable<P>>), dim3(tiles),
-                               dim3(kRsaBlock), 0, st, acc, small<P>(g), p, tab);
-        else
-            hipLaunchKernelGGL((rsa_seg_kernel<0, A.value, SA.value, PtrTable>), dim3(tiles), dim3(kRsaBlock),
-                               0, st, acc, g, p, tab);
-    });
-}
-}  // namespace
-
-int launch_reduce_coalesced(float* acc, const PtrTable& g, const Segment* segs, int n, int p,
+int launch_reduce_coalesced(float* acc, const PtrTable& grads, const Segment* segs, int n, int p,
                             bool accumulate, void* stream)
 {
     hipStream_t st = (hipStream_t)stream;
     constexpr size_t kTileElems = (size_t)kRsaBlock * 8;
+    PtrTable g = grads;
+    const size_t base_lead = align_gradient_pointers(g, p, 2);
     for (int first = 0; first < n; first += kMaxSeg) {
         ReduceSegTable tab;
         tab.n = n - first < kMaxSeg ? n - first : kMaxSeg;
@@ -1138,137 +1074,54 @@ int launch_reduce_coalesced(float* acc, const PtrTable& g, const Segment* segs, 
         for (int t = 0; t < tab.n; ++t) {
             const Segment& sg = segs[first + t];
             elements += sg.numel;
+            // position of the segment's first element in the rounded-down buffers; its virtual
+            // element 0 is the even position at or below it
+            const size_t src = sg.src_offset + base_lead;
+            const unsigned lead = (unsigned)(src & 1);
             tab.tile_begin[t] = (unsigned)tiles;
-            tab.seg[t].count = sg.numel;
-            tab.seg[t].src_off = sg.src_offset;
-            tab.seg[t].dst_off = sg.dst_offset;
-            tiles += (sg.numel + kTileElems - 1) / kTileElems;
+            tab.seg[t].lead = lead;
+            tab.seg[t].pad = 0;
+            tab.seg[t].end = lead + sg.numel;
+            tab.seg[t].src0 = src - lead;
+            tab.seg[t].dst = sg.dst_offset;
+            if (sg.numel) tiles += (lead + sg.numel + kTileElems - 1) / kTileElems;
+            else tab.seg[t].end = 0;
             if (tiles > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
         }
         for (int t = tab.n; t <= kMaxSeg; ++t) tab.tile_begin[t] = 0xFFFFFFFFu;
         if (tiles == 0) continue;
-        switch (p) {
-            case 1: rsa_seg_launch<1>(acc, g, p, tab, (unsigned)tiles, accumulate, stream_acc(elements), st); break;
-            case 2: rsa_seg_launch<2>(acc, g, p, tab, (unsigned)tiles, accumulate, stream_acc(elements), st); break;
-            case 4: rsa_seg_launch<4>(acc, g, p, tab, (unsigned)tiles, accumulate, stream_acc(elements), st); break;
-            case 8: rsa_seg_launch<8>(acc, g, p, tab, (unsigned)tiles, accumulate, stream_acc(elements), st); break;
-            case 16: rsa_seg_launch<16>(acc, g, p, tab, (unsigned)tiles, accumulate, stream_acc(elements), st); break;
-            case 32: rsa_seg_launch<32>(acc, g, p, tab, (unsigned)tiles, accumulate, stream_acc(elements), st); break;
-            default: rsa_seg_launch<0>(acc, g, p, tab, (unsigned)tiles, accumulate, stream_acc(elements), st);
-        }
-        if (int e = launch_status()) return e;
+        const int err = dispatch2(accumulate, stream_acc(elements), [&](auto A, auto SA) {
+            return dispatch_group(p, [&](auto P) {
+                if constexpr (P.value > 0)
+                    return launch(rsa_seg_kernel<P.value, A.value, SA.value, SmallTable<P.value>>,
+                                  dim3((unsigned)tiles), dim3(kRsaBlock), st, acc, small<P.value>(g), p, tab);
+                else
+                    return launch(rsa_seg_kernel<0, A.value, SA.value, PtrTable>, dim3((unsigned)tiles),
+                                  dim3(kRsaBlock), st, acc, g, p, tab);
+            });
+        });
+        if (err) return err;
     }
     return 0;
 }
-
-namespace {
-template <int R, bool BF16>
-void avg_adam_launch(float* w, float* m, float* v, uint16_t* pb, const PtrTable& a, int r, float scale,
-                     size_t nvec, const AdamScalars& hp, unsigned blocks, hipStream_t st)
-{
-    if constexpr (R > 0)
-        hipLaunchKernelGGL((avg_adam_vec_kernel<R, BF16, SmallTable<R>>), dim3(blocks), dim3(kAdamBlock), 0,
-                           st, w, m, v, pb, small<R>(a), r, scale, nvec, hp);
-    else
-        hipLaunchKernelGGL((avg_adam_vec_kernel<0, BF16, PtrTable>), dim3(blocks), dim3(kAdamBlock), 0, st,
-                           w, m, v, pb, a, r, scale, nvec, hp);
-}
-
-template <bool BF16>
-void avg_adam_dispatch(float* w, float* m, float* v, uint16_t* pb, const PtrTable& a, int r, float scale,
-                       size_t nvec, const AdamScalars& hp, unsigned blocks, hipStream_t st)
-{
-    switch (r) {
-        case 1: avg_adam_launch<1, BF16>(w, m, v, pb, a, r, scale, nvec, hp, blocks, st); break;
-        case 2: avg_adam_launch<2, BF16>(w, m, v, pb, a, r, scale, nvec, hp, blocks, st); break;
-        case 4: avg_adam_launch<4, BF16>(w, m, v, pb, a, r, scale, nvec, hp, blocks, st); break;
-        case 8: avg_adam_launch<8, BF16>(w, m, v, pb, a, r, scale, nvec, hp, blocks, st); break;
-        default: avg_adam_launch<0, BF16>(w, m, v, pb, a, r, scale, nvec, hp, blocks, st);
-    }
-}
-}  // namespace
 
 int launch_avg_adam(float* master, float* exp_avg, float* exp_avg_sq, uint16_t* param_bf16,
                     const PtrTable& copies, int r, float scale, size_t count, const AdamScalars& hp,
-                    bool vec16, void* stream)
+                    void* stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    const size_t nvec = vec16 ? count / 4 : 0;
     unsigned blocks = 0;
-    if (nvec) {
-        if (int e = grid_for(nvec, kAdamBlock, MICS_ADAM_BPC, &blocks)) return e;
-        if (param_bf16)
-            avg_adam_dispatch<true>(master, exp_avg, exp_avg_sq, param_bf16, copies, r, scale, nvec, hp,
-                                    blocks, st);
-        else
-            avg_adam_dispatch<false>(master, exp_avg, exp_avg_sq, param_bf16, copies, r, scale, nvec, hp,
-                                     blocks, st);
-        if (int e = launch_status()) return e;
-    }
-    const size_t first = nvec * 4;
-    if (first < count) {
-        if (int e = grid_for(count - first, kBlock, kTailBpc, &blocks)) return e;
-        if (param_bf16)
-            hipLaunchKernelGGL(avg_adam_scalar_kernel<true>, dim3(blocks), dim3(kBlock), 0, st, master,
-                               exp_avg, exp_avg_sq, param_bf16, copies, r, scale, first, count, hp);
-        else
-            hipLaunchKernelGGL(avg_adam_scalar_kernel<false>, dim3(blocks), dim3(kBlock), 0, st, master,
-                               exp_avg, exp_avg_sq, param_bf16, copies, r, scale, first, count, hp);
-        if (int e = launch_status()) return e;
-    }
-    return 0;
-}
-
-namespace {
-template <int KIND, int P, bool ACCUM>
-void rsa_typed_launch(float* acc, const PtrTable& g, int p, size_t nvec, bool sa, unsigned blocks,
-                      hipStream_t st)
-{
-    dispatch2(sa, false, [&](auto SA, auto) {
-        if constexpr (P > 0)
-            hipLaunchKernelGGL((rsa_typed_vec_kernel<KIND, P, ACCUM, SA.value, SmallTable<P>>), dim3(blocks),
-                               dim3(kRsaBlock), 0, st, acc, small<P>(g), p, nvec);
-        else
-            hipLaunchKernelGGL((rsa_typed_vec_kernel<KIND, 0, ACCUM, SA.value, PtrTable>), dim3(blocks),
-                               dim3(kRsaBlock), 0, st, acc, g, p, nvec);
-    });
-}
-
-template <int KIND, bool ACCUM>
-int rsa_typed_all(float* acc, const PtrTable& g, size_t count, int p, bool vec16, hipStream_t st)
-{
-    constexpr size_t EPV = KIND == 1 ? 8 : 4;
-    const size_t nvec = vec16 ? count / EPV : 0;
-    unsigned blocks = 0;
-    if (nvec) {
-        if (int e = grid_for(nvec, kRsaBlock, MICS_RSA_BPC, &blocks)) return e;
-        switch (p) {
-            case 8: rsa_typed_launch<KIND, 8, ACCUM>(acc, g, p, nvec, stream_acc(count), blocks, st); break;
-            case 16: rsa_typed_launch<KIND, 16, ACCUM>(acc, g, p, nvec, stream_acc(count), blocks, st); break;
-            default: rsa_typed_launch<KIND, 0, ACCUM>(acc, g, p, nvec, stream_acc(count), blocks, st);
+    if (int e = grid_for((count + 3) / 4, kFusedBlock, MICS_ADAM_BPC, &blocks)) return e;
+    return dispatch2(param_bf16 != nullptr, false, [&](auto BF, auto) {
+        const dim3 gr(blocks), bl(kFusedBlock);
+        switch (r) {
+            case 1: return launch(avg_adam_kernel<1, BF.value, SmallTable<1>>, gr, bl, st, master, exp_avg, exp_avg_sq, param_bf16, small<1>(copies), r, scale, count, hp);
+            case 2: return launch(avg_adam_kernel<2, BF.value, SmallTable<2>>, gr, bl, st, master, exp_avg, exp_avg_sq, param_bf16, small<2>(copies), r, scale, count, hp);
+            case 4: return launch(avg_adam_kernel<4, BF.value, SmallTable<4>>, gr, bl, st, master, exp_avg, exp_avg_sq, param_bf16, small<4>(copies), r, scale, count, hp);
+            case 8: return launch(avg_adam_kernel<8, BF.value, SmallTable<8>>, gr, bl, st, master, exp_avg, exp_avg_sq, param_bf16, small<8>(copies), r, scale, count, hp);
+            default: return launch(avg_adam_kernel<0, BF.value, PtrTable>, gr, bl, st, master, exp_avg, exp_avg_sq, param_bf16, copies, r, scale, count, hp);
         }
-        if (int e = launch_status()) return e;
-    }
-    const size_t first = nvec * EPV;
-    if (first < count) {
-        if (int e = grid_for(count - first, kBlock, kTailBpc, &blocks)) return e;
-        hipLaunchKernelGGL((rsa_typed_scalar_kernel<KIND, ACCUM>), dim3(blocks), dim3(kBlock), 0, st, acc, g,
-                           p, first, count);
-        if (int e = launch_status()) return e;
-    }
-    return 0;
-}
-}  // namespace
-
-int launch_reduce_scatter_accum_typed(float* acc, const PtrTable& g, size_t count, int p,
-                                      bool accumulate, int kind, bool vec16, void* stream)
-{
-    hipStream_t st = (hipStream_t)stream;
-    if (kind == 1)
-        return accumulate ? rsa_typed_all<1, true>(acc, g, count, p, vec16, st)
-                          : rsa_typed_all<1, false>(acc, g, count, p, vec16, st);
-    return accumulate ? rsa_typed_all<2, true>(acc, g, count, p, vec16, st)
-                      : rsa_typed_all<2, false>(acc, g, count, p, vec16, st);
+    });
 }
 
 }  // namespace mics

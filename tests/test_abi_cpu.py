@@ -7,7 +7,7 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "mics.h")
+HEADERS = [os.path.join(ROOT, "include", name) for name in ("mics.h", "mics_tuning.h")]
 
 mics = pytest.importorskip("paper_2205_00119_amd", reason="libmics.so is not built")
 
@@ -16,7 +16,7 @@ BUF = 1 << 24                # pretend buffers are spaced far apart
 
 
 def declared_functions():
-    text = open(HEADER).read()
+    text = "".join(open(h).read() for h in HEADERS)
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return re.findall(r"\b(mics_\w+)\s*\(", text)
 
@@ -150,7 +150,7 @@ def test_launch_knob_range():
 def test_header_is_valid_c99_and_cxx(tmp_path):
     import subprocess
     c = tmp_path / "use.c"
-    c.write_text('#include "mics.h"\nint f(void) { mics_segment s = {1, 1, 0, 0}; (void)s; '
+    c.write_text('#include "mics.h"\n#include "mics_tuning.h"\nint f(void) { mics_segment s = {1, 1, 0, 0}; (void)s; '
                  'return mics_version() + MICS_MAX_GROUP + MICS_ERR_HIP + MICS_DTYPE_F32; }\n')
     inc = os.path.join(ROOT, "include")
     subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", f"-I{inc}", str(c)],
