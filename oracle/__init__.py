@@ -20,9 +20,6 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "mics_oracle.c")
 _LIB = os.path.join(_HERE, "libmics_oracle.so")
-# The mutation test (tests/test_oracle_mutants.py) points this at deliberately broken builds of
-# the oracle to show that the pins notice; nothing else sets it.
-_LIB_OVERRIDE = os.environ.get("MICS_ORACLE_LIB")
 
 CFLAGS = ["-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
           "-shared", "-fPIC", "-Wall", "-Wextra"]
@@ -38,17 +35,24 @@ def build(force: bool = True, src: str = _SRC, out: str = _LIB) -> str:
 
 
 _lib = None
+_lib_path = _LIB
+
+
+def use_library(path: str) -> None:
+    """Load the oracle from another shared object from now on.  Only the mutation test
+    (tests/test_oracle_mutants.py, through the --oracle-lib option of tests/conftest.py) calls
+    this, with deliberately broken builds, to show that the pins notice; nothing reads the
+    environment."""
+    global _lib, _lib_path
+    _lib, _lib_path = None, path
 
 
 def _load():
     global _lib
     if _lib is None:
-        if _LIB_OVERRIDE:
-            lib = ctypes.CDLL(_LIB_OVERRIDE)
-        else:
-            if not os.path.exists(_LIB):
-                build()
-            lib = ctypes.CDLL(_LIB)
+        if _lib_path == _LIB and not os.path.exists(_LIB):
+            build()
+        lib = ctypes.CDLL(_lib_path)
         vp, sz, i32, f32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_float
         lib.orc_set_threads.argtypes = [i32]
         lib.orc_set_threads.restype = i32

@@ -528,17 +528,17 @@ __device__ __forceinline__ void rsa_partial(float* s, const Tab& g, int p, size_
     }
 }
 
-// acc_e[0 .. EPL) = (ACCUM ? acc_e : +0) + partial sum at virtual element `elem`.
+// a[0 .. EPL) = (ACCUM ? acc_e[0 .. EPL) : +0) + partial sum at virtual element `elem`.
 // SA ("stream the accumulator"): non-temporal accumulator loads and stores.  An accumulator
 // that fits the 256 MB Infinity Cache is best left cacheable -- its stores are absorbed there
 // and the next micro-step finds it again (plain/plain 6.3 TB/s, NT/NT 6.1 at S = 50 M) -- while
 // a larger one is best streamed past the caches (NT/NT 5.8 TB/s, plain/plain 5.4, and the
 // mixed NT-load/plain-store 5.1 at S = 200 M); the launcher picks by size.
 template <int KIND, int VEC, int P, int BATCH, bool ACCUM, bool SA, typename Tab>
-__device__ __forceinline__ void rsa_update(float* __restrict__ acc_e, const Tab& g, int p, size_t elem)
+__device__ __forceinline__ void rsa_sum(float (&a)[VEC * GradFormat<KIND>::kPerDword], const float* acc_e,
+                                        const Tab& g, int p, size_t elem)
 {
     constexpr int EPL = VEC * GradFormat<KIND>::kPerDword;
-    float a[EPL];
     #pragma unroll
     for (int e = 0; e < EPL; ++e) a[e] = 0.0f;
     if (ACCUM) ld_f32<EPL, SA>(a, acc_e);          // issued before the gradient loads are consumed
@@ -546,7 +546,6 @@ __device__ __forceinline__ void rsa_update(float* __restrict__ acc_e, const Tab&
     rsa_partial<KIND, VEC, P, BATCH>(s, g, p, elem);
     #pragma unroll
     for (int e = 0; e < EPL; ++e) a[e] = a[e] + s[e];
-    st_f32<EPL, SA>(acc_e, a);
 }
 
 template <int KIND, bool ACCUM, typename Tab>
@@ -557,17 +556,50 @@ __device__ __forceinline__ void rsa_element(float* acc_e, const Tab& g, int p, s
     *acc_e = (ACCUM ? *acc_e : 0.0f) + partial;
 }
 
-// The lane's virtual elements [v0, v0 + EPL) against the call's range [lead, end): acc_v is
-// the accumulator address of virtual element 0 (never dereferenced outside the range).
-template <int KIND, int VEC, int P, int BATCH, bool ACCUM, bool SA, typename Tab>
-__device__ __forceinline__ void rsa_lane(float* acc, const Tab& g, int p, size_t v0, size_t lead, size_t end)
+// The lane's virtual elements [v0, v0 + EPL) of a call (or segment) whose elements are the
+// virtual range [lead, end): `acc` is the accumulator address of virtual element `lead`, and
+// virtual element e sits at element src0 + e of every rank buffer.  Consecutive lanes of a
+// wavefront hold consecutive v0, and every lane of the wavefront gets here (lanes past `end`
+// find nothing to do).
+//
+// Streamed accumulators of 8-element lanes are stored through LDS: a lane's two 128-bit
+// stores are 32 bytes apart, so each store instruction of the wavefront would fill every
+// other 16 bytes of its cache lines, and with non-temporal stores about one line in ten left
+// the L2 between the two halves (WRITE_SIZE 1.10 x the accumulator's bytes at 800 M elements).
+// Passing the results through 2 KiB of LDS per wavefront lets every store instruction cover
+// one contiguous KiB.  Only wavefronts whose 64 lanes all hold full vectors take this path.
+template <int KIND, int VEC, int P, int BATCH, bool ACCUM, bool SA, int BLOCK, typename Tab>
+__device__ __forceinline__ void rsa_lane(float* acc, const Tab& g, int p, size_t src0, size_t v0,
+                                         size_t lead, size_t end)
 {
-    constexpr size_t EPL = VEC * GradFormat<KIND>::kPerDword;
-    if (v0 >= lead && v0 + EPL <= end) {
-        rsa_update<KIND, VEC, P, BATCH, ACCUM, SA>(acc + (v0 - lead), g, p, v0);
+    constexpr int EPL = VEC * GradFormat<KIND>::kPerDword;
+    const bool full = v0 >= lead && v0 + EPL <= end;
+    if constexpr (SA && EPL == 8) {
+        if (__builtin_amdgcn_ballot_w64(full) == ~0ull) {       // wavefront-uniform
+            __shared__ f32x4 stage[BLOCK * 2];
+            const unsigned lane = threadIdx.x & 63u;
+            f32x4* mine = stage + (threadIdx.x - lane) * 2;      // this wavefront's 128 vectors
+            float* acc_e = acc + (v0 - lead);
+            float a[EPL];
+            rsa_sum<KIND, VEC, P, BATCH, ACCUM, SA>(a, acc_e, g, p, src0 + v0);
+            mine[2 * lane] = f32x4{a[0], a[1], a[2], a[3]};
+            mine[2 * lane + 1] = f32x4{a[4], a[5], a[6], a[7]};
+            // LDS operations of one wavefront complete in order: no barrier between these
+            const f32x4 r0 = mine[lane], r1 = mine[64 + lane];
+            f32x4_a4* wave_base = (f32x4_a4*)(acc_e - 8 * lane);
+            MICS_ST(true, wave_base + lane, r0);
+            MICS_ST(true, wave_base + 64 + lane, r1);
+            return;
+        }
+    }
+    if (full) {
+        float* acc_e = acc + (v0 - lead);
+        float a[EPL];
+        rsa_sum<KIND, VEC, P, BATCH, ACCUM, SA>(a, acc_e, g, p, src0 + v0);
+        st_f32<EPL, SA>(acc_e, a);
     } else {
         const size_t lo = v0 > lead ? v0 : lead, hi = v0 + EPL < end ? v0 + EPL : end;
-        for (size_t e = lo; e < hi; ++e) rsa_element<KIND, ACCUM>(acc + (e - lead), g, p, e);
+        for (size_t e = lo; e < hi; ++e) rsa_element<KIND, ACCUM>(acc + (e - lead), g, p, src0 + e);
     }
 }
 
@@ -581,8 +613,8 @@ __global__ __launch_bounds__(VEC == 4 ? kRsaBlock : kNarrowBlock) void rsa_kerne
     const size_t end = (size_t)lead + count;
     const size_t nlanes = (end + EPL - 1) / EPL;
     const size_t stride = (size_t)gridDim.x * BLOCK;
-    for (size_t i = (size_t)blockIdx.x * BLOCK + threadIdx.x; i < nlanes; i += stride)
-        rsa_lane<KIND, VEC, P, BATCH, ACCUM, SA>(acc, g, p, i * EPL, lead, end);
+    for (size_t base = (size_t)blockIdx.x * BLOCK; base < nlanes; base += stride)   // workgroup-uniform
+        rsa_lane<KIND, VEC, P, BATCH, ACCUM, SA, BLOCK>(acc, g, p, 0, (base + threadIdx.x) * EPL, lead, end);
 }
 
 // Coalesced form (many separately sharded tensors in one launch, bf16): workgroup x works on
@@ -608,16 +640,8 @@ __global__ __launch_bounds__(kRsaBlock) void rsa_seg_kernel(
     const int t = segment_of(tab.tile_begin, x);
     const size_t end = tab.seg[t].end, lead = tab.seg[t].lead;
     const size_t v0 = ((size_t)(x - tab.tile_begin[t]) * kRsaBlock + threadIdx.x) * 8;
-    if (v0 >= end) return;
-    // the segment's virtual element e sits at element src0 + e of every rank buffer
-    const size_t src0 = tab.seg[t].src0;
-    float* acc_t = acc + tab.seg[t].dst;
-    if (v0 >= lead && v0 + 8 <= end) {
-        rsa_update<0, 4, P, MICS_RSA_BATCH, ACCUM, SA>(acc_t + (v0 - lead), g, p, src0 + v0);
-    } else {
-        const size_t lo = v0 > lead ? v0 : lead, hi = v0 + 8 < end ? v0 + 8 : end;
-        for (size_t e = lo; e < hi; ++e) rsa_element<0, ACCUM>(acc_t + (e - lead), g, p, src0 + e);
-    }
+    rsa_lane<0, 4, P, MICS_RSA_BATCH, ACCUM, SA, kRsaBlock>(acc + tab.seg[t].dst, g, p, tab.seg[t].src0, v0, lead,
+                                                            end);
 }
 
 // ---------------------------------------------------------------------------
@@ -803,7 +827,7 @@ __global__ __launch_bounds__(kFusedBlock) void avg_adam_kernel(
 
 std::atomic<int> g_blocks_per_cu{0};
 // Accumulators (reduce) and outputs (replica average) up to this size are left cacheable,
-// larger ones are streamed (see rsa_update).
+// larger ones are streamed (see rsa_sum).
 constexpr size_t kDefaultStreamBytes = 224u << 20;
 std::atomic<size_t> g_stream_bytes{kDefaultStreamBytes};
 

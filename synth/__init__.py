@@ -41,6 +41,9 @@ def layer_elems(h: int) -> int:
 
 
 def shard_elems(n: int, p: int, align: int = 8) -> int:
+    """Workload geometry: how the synthetic layers are cut into p shards (equal parts, rounded up
+    to `align` elements, the tail padded).  The paper leaves the padding rule open; this is the
+    caller-side convention of the configurations, not arithmetic on data."""
     per = -(-n // p)
     return -(-per // align) * align
 
@@ -142,11 +145,12 @@ def coalesced_layout(numels, p: int, k: int, align: int = 8, flat_align: int = 1
 
 # ---- tables --------------------------------------------------------------------------
 
-def _f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
-    """Generator-private float32 -> bf16 bits (nearest even) for finite table values."""
-    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
-    u = u + 0x7FFF + ((u >> 16) & 1)
-    return (u >> 16).astype(np.uint16)
+def _bf16_grid_bits(x: np.ndarray) -> np.ndarray:
+    """Bit patterns of bf16 values for the table: the upper half of each float32 (the lower half
+    is cut off).  This only puts the table entries on the bf16 grid -- it is deliberately not the
+    round-to-nearest-even narrowing that the method's Adam step performs, which lives in the
+    library and in the oracle, each on its own."""
+    return (np.ascontiguousarray(x, dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
 
 
 def normal_table(sigma: float, elem: str) -> np.ndarray:
@@ -157,14 +161,14 @@ def normal_table(sigma: float, elem: str) -> np.ndarray:
     if elem == "f32":
         return f
     if elem == "bf16":
-        return _f32_to_bf16_bits(f)
+        return _bf16_grid_bits(f)
     raise ValueError(elem)
 
 
 def small_int_table(lo: int, hi: int, elem: str) -> np.ndarray:
     """Table of integers in [lo, hi] (exactly representable): sums over them are exact."""
     vals = (lo + (np.arange(TABLE_SLOTS) % (hi - lo + 1))).astype(np.float32)
-    return vals if elem == "f32" else _f32_to_bf16_bits(vals)
+    return vals if elem == "f32" else _bf16_grid_bits(vals)
 
 
 # ---- stream keys -----------------------------------------------------------------------

@@ -26,9 +26,12 @@ def _need_gpu(gen):
     torch.cuda.empty_cache()
 
 
-def windows(n, extra_points=(), seed=0, n_random=6, win=WIN):
-    """Element ranges [a, b) inside [0, n): both ends, around the given points, random ones."""
+def windows(n, extra_points=(), seed=0, n_random=None, win=WIN):
+    """Element ranges [a, b) inside [0, n): both ends, around the given points, and random ones
+    that cover 1 % of the range (at least 6 of them) unless n_random says otherwise."""
     rng = np.random.default_rng(seed)
+    if n_random is None:
+        n_random = max(6, -(-n // (100 * win)))
     starts = {0, max(n - win, 0)}
     for pt in extra_points:
         starts.add(min(max(pt - win // 2, 0), max(n - win, 0)))
@@ -133,7 +136,7 @@ def test_reorder_full_size(orc, gen, name):
             assert int(src.to(torch.int64).sum()) == int(dst.to(torch.int64).sum())
 
 
-def run_rank_pipeline(orc, gen, cfg, rank, count, offset, n_windows=6):
+def run_rank_pipeline(orc, gen, cfg, rank, count, offset, boundaries=()):
     """s reduce-scatter-accumulates, the replica average and one Adam step on `count` elements
     starting at global element `offset`, checked on sampled windows."""
     p, r, s = cfg.p, cfg.r, cfg.s
@@ -164,7 +167,7 @@ def run_rank_pipeline(orc, gen, cfg, rank, count, offset, n_windows=6):
     # MICS_TEST_FULL=1 checks every element instead of sampled windows (minutes of oracle time)
     spans = ([(a, min(a + (1 << 22), count)) for a in range(0, count, 1 << 22)]
              if os.environ.get("MICS_TEST_FULL") == "1" else
-             windows(count, extra_points=[count // 2], seed=cfg.seed + rank, n_random=n_windows))
+             windows(count, extra_points=[count // 2, *boundaries], seed=cfg.seed + rank))
     for a, b in spans:
         n = b - a
         acc_ref = np.empty(n, np.float32)
@@ -201,13 +204,14 @@ def run_rank_pipeline(orc, gen, cfg, rank, count, offset, n_windows=6):
                                        ("h8192", 5)])
 def test_rank_view_pipeline_full_size(orc, gen, name, rank):
     cfg = gen.CONFIGS[name]
-    assert run_rank_pipeline(orc, gen, cfg, rank, cfg.S, rank * cfg.S) > 0
+    assert run_rank_pipeline(orc, gen, cfg, rank, cfg.S, rank * cfg.S) >= min(cfg.S // 100, 6 * WIN)
 
 
 def test_group_view_full_size_h8192(orc, gen):
     # all p shards in one call: N_pad = 805,412,864 elements per launch, 25.8 GB of gradients
     cfg = gen.CONFIGS["h8192"]
-    assert run_rank_pipeline(orc, gen, cfg, 0, cfg.N_pad, 0, n_windows=10) > 0
+    checked = run_rank_pipeline(orc, gen, cfg, 0, cfg.N_pad, 0, boundaries=[g * cfg.S for g in range(1, cfg.p)])
+    assert checked >= cfg.N_pad // 100
 
 
 def test_coalesced_layer_full_size_h8192(orc, gen):

@@ -100,11 +100,17 @@ RSA_CASES = [
     (3, 30000, 0, 30000, 2, 0),               # p without an unrolled kernel
     (5, 30000, 16, 20001, 2, 0),
     (32, 20000, 160, 15000, 2, 0),            # cfg-4 group size
-    (128, 4096, 0, 4096, 1, 0),               # largest group
+    (32, 150000, 160, 140003, 2, 0),          # ... beyond the small-message kernel: two batches of 16 loads
+    (128, 4096, 0, 4096, 1, 0),               # largest group (small message: one dword per lane)
+    (128, 34000, 8, 33001, 1, 0),             # largest group, 128-bit kernel: 8 batches
     (64, 40000, 64, 39000, 2, 0),             # 8 nodes of 8 (the paper's 50B-parameter group)
-    (40, 20000, 0, 20000, 2, 0),              # one full batch of 32 loads plus a partial one
-    (4, 30000, 3, 20000, 2, 0),               # offset not a multiple of 8: element path
-    (8, 30000, 0, 30000, 2, 1),               # buffers off 16-byte alignment: element path
+    (64, 9000, 3, 8190, 2, 1),                # small message, odd offset, accumulator off by 4 bytes
+    (40, 20000, 0, 20000, 2, 0),              # any-p kernels, small message
+    (40, 112000, 0, 110003, 2, 0),            # any-p kernels, 128-bit loads: batches of 16, 16, 8
+    (4, 30000, 3, 20000, 2, 0),               # odd offset: pointers rounded down, first lane element-wise
+    (8, 30000, 0, 30000, 2, 1),               # buffers and accumulator off 16-byte alignment
+    (16, 30000, 5, 1, 2, 0),                  # a single element at an odd offset
+    (16, 30000, 5, 2, 2, 3),
 ]
 
 
@@ -639,3 +645,167 @@ def test_calls_on_two_streams_ordered_by_events(orc, gen):
     pbr = orc.adam_shard(wr, mr, vr, ref, step=1, f32=True, **HP)
     assert np.array_equal(w.cpu().numpy().view(np.uint32), wr.view(np.uint32))
     assert np.array_equal(pb.cpu().numpy().view(np.uint16), pbr)
+
+
+# ---- any element alignment ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("p,count,skews,acc_skew", [
+    (16, 50003, [q % 2 for q in range(16)], 0),        # mixed parity: 2-byte aligned 128-bit loads
+    (16, 50003, [(3 * q) % 8 for q in range(16)], 1),
+    (8, 20000, [1] * 8, 2),                             # all odd: rounded down together
+    (40, 9001, [q % 3 for q in range(40)], 3),          # small-message kernel, mixed parity
+    (5, 7, [0, 1, 2, 3, 4], 1),
+])
+def test_reduce_scatter_accum_with_individually_shifted_buffers(orc, gen, p, count, skews, acc_skew):
+    tab = gen.normal_table(1e-3, "bf16")
+    acc = Guarded(count, np.float32, skew=acc_skew)
+    ref = np.full(count, np.nan, np.float32)
+    for t in range(2):
+        host = [gen.fill_host(gen.stream_key(1300, gen.ROLE_GRAD, 0, t, q), 0, count, tab) for q in range(p)]
+        dev = [Guarded(count, np.uint16, skew=skews[q], fill=host[q]) for q in range(p)]
+        mics.mics_reduce_scatter_accum(acc.t, [d.t for d in dev], 0, count, t > 0)
+        torch.cuda.synchronize()
+        orc.reduce_scatter_accum(ref, host, 0, t > 0)
+        assert all(d.guards_intact() for d in dev)
+    assert np.array_equal(acc.numpy().view(np.uint32), ref.view(np.uint32))
+    assert acc.guards_intact()
+
+
+@pytest.mark.parametrize("r,count", [(8, 40003), (3, 20001), (20, 9000)])
+def test_replica_average_and_adam_with_individually_shifted_buffers(orc, gen, r, count):
+    tab = gen.normal_table(3e-2, "f32")
+    host = [gen.fill_host(gen.stream_key(1400, gen.ROLE_ACC, c), 0, count, tab) for c in range(r)]
+    dev = [Guarded(count, np.float32, skew=c % 4, fill=h) for c, h in enumerate(host)]
+    out = Guarded(count, np.float32, skew=3)
+    scale = float(np.float32(1.0 / (r * 16 * 12)))
+    mics.mics_replica_average(out.t, [d.t for d in dev], count, scale)
+    torch.cuda.synchronize()
+    want = orc.replica_average(host, scale)
+    assert np.array_equal(out.numpy().view(np.uint32), want.view(np.uint32))
+    assert out.guards_intact() and all(d.guards_intact() for d in dev)
+
+    w0 = gen.fill_host(gen.stream_key(1400, gen.ROLE_MASTER), 0, count, gen.normal_table(0.02, "f32"))
+    zeros = np.zeros(count, np.float32)
+    wr, mr, vr = w0.copy(), zeros.copy(), zeros.copy()
+    pbr = orc.adam_shard(wr, mr, vr, want, step=2, f32=True, **HP)
+    for fused in (False, True):
+        w, m, v = (Guarded(count, np.float32, skew=sk, fill=x) for sk, x in ((1, w0), (2, zeros), (0, zeros)))
+        pb = Guarded(count, np.uint16, skew=5)
+        if fused:
+            mics.mics_replica_average_adam_shard(w.t, m.t, v.t, pb.t, [d.t for d in dev], count, scale,
+                                                 step=2, **HP)
+        else:
+            mics.mics_adam_shard(w.t, m.t, v.t, pb.t, out.t, count, step=2, **HP)
+        torch.cuda.synchronize()
+        assert np.array_equal(w.numpy().view(np.uint32), wr.view(np.uint32))
+        assert np.array_equal(m.numpy().view(np.uint32), mr.view(np.uint32))
+        assert np.array_equal(v.numpy().view(np.uint32), vr.view(np.uint32))
+        assert np.array_equal(pb.numpy(), pbr)
+        assert all(x.guards_intact() for x in (w, m, v, pb))
+
+
+# ---- the Adam step writes straight into the stage-1 layout of the next gather --------------------------
+
+@pytest.mark.parametrize("p,k,S,fused", [(4, 2, 4104, False), (16, 8, 2050, True), (8, 4, 4099, False),
+                                          (8, 4, 4099, True), (6, 6, 1001, True), (6, 1, 1001, False)])
+def test_adam_writes_bf16_in_stage1_layout_of_the_next_gather(orc, gen, p, k, S, fused):
+    """Section 3.3: after the inter-node stage, the buffer of local rank l holds T_l = [C_l, C_{k+l},
+    ...].  Rank g = j*k + l writes its updated bf16 shard directly at T_l + j*S (on the wire: the
+    place the inter-node all-gather would put it), so no copy sits between the update and the next
+    parameter gather; gathering those buffers must give the bf16 of the whole updated parameter."""
+    r, n = 2, p * S - 5
+    nodes = p // k
+    scale = float(np.float32(1.0 / (r * p)))
+    tab = gen.normal_table(1e-3 * p ** 0.5, "f32")
+    copies_h = [gen.fill_host(gen.stream_key(1500, gen.ROLE_ACC, c), 0, p * S, tab) for c in range(r)]
+    w0 = gen.fill_host(gen.stream_key(1500, gen.ROLE_MASTER), 0, p * S, gen.normal_table(0.02, "f32"))
+    # the whole-buffer update by the oracle
+    w_ref, m_ref, v_ref = w0.copy(), np.zeros(p * S, np.float32), np.zeros(p * S, np.float32)
+    pb_ref = orc.adam_shard(w_ref, m_ref, v_ref, orc.replica_average(copies_h, scale), step=1, f32=True, **HP)
+
+    T = [Guarded(nodes * S, np.uint16) for _ in range(k)]
+    for g in range(p):
+        j, l = divmod(g, k)
+        sl = slice(g * S, (g + 1) * S)
+        w, m, v = upload(w0[sl].copy()), torch.zeros(S, device="cuda:0"), torch.zeros(S, device="cuda:0")
+        copies = [upload(c[sl].copy()) for c in copies_h]
+        dest = T[l].t[j * S:(j + 1) * S]
+        if fused:
+            mics.mics_replica_average_adam_shard(w, m, v, dest, copies, S, scale, step=1, **HP)
+        else:
+            avg = torch.empty(S, dtype=torch.float32, device="cuda:0")
+            mics.mics_replica_average(avg, copies, S, scale)
+            mics.mics_adam_shard(w, m, v, dest, avg, S, step=1, **HP)
+        torch.cuda.synchronize()
+        assert np.array_equal(w.cpu().numpy().view(np.uint32), w_ref[sl].view(np.uint32))
+    assert all(t.guards_intact() for t in T)
+    flat = Guarded(n, np.uint16)
+    mics.mics_hier_gather_reorder(flat.t, [t.t for t in T], n, S, p, k, 2)
+    torch.cuda.synchronize()
+    assert np.array_equal(flat.numpy(), pb_ref[:n])
+    assert flat.guards_intact()
+
+
+# ---- accumulators and outputs larger than the cache: the streaming kernels ------------------------------
+
+def test_streaming_kernels_give_the_same_results(orc, gen):
+    """Accumulators (reduce) and outputs (average) above 224 MiB take kernels with non-temporal
+    accumulator accesses.  With the threshold at one byte every call here takes them: flat, odd
+    offsets, unrolled and any-p groups, small messages, fp16 / fp32 gradients, the coalesced form,
+    unrolled and any-r averages."""
+    tab = gen.normal_table(1e-3, "bf16")
+    try:
+        mics.mics_set_stream_threshold_bytes(1)
+        for p, off, count in [(16, 0, 40003), (2, 1, 30000), (1, 0, 5000), (4, 3, 9000), (8, 0, 20000),
+                              (32, 0, 140000), (40, 5, 110000), (64, 1, 8000)]:
+            total = off + count + 3
+            acc = Guarded(count, np.float32)
+            ref = np.full(count, np.nan, np.float32)
+            for t in range(2):
+                host = [gen.fill_host(gen.stream_key(1600 + p, gen.ROLE_GRAD, 0, t, q), 0, total, tab)
+                        for q in range(p)]
+                mics.mics_reduce_scatter_accum(acc.t, [upload(h) for h in host], off, count, t > 0)
+                torch.cuda.synchronize()
+                orc.reduce_scatter_accum(ref, host, off, t > 0)
+            assert np.array_equal(acc.numpy().view(np.uint32), ref.view(np.uint32)), (p, off, count)
+            assert acc.guards_intact()
+        for name, dtype, code, np_dt in (("f16", mics.MICS_DTYPE_F16, orc.DTYPE_F16, np.uint16),
+                                         ("f32", mics.MICS_DTYPE_F32, orc.DTYPE_F32, np.float32)):
+            t16 = (gen.normal_table(3e-5, "f32").astype(np.float16).view(np.uint16) if name == "f16"
+                   else gen.normal_table(1e-3, "f32"))
+            for p, off, count in [(16, 0, 30001), (8, 2, 20000), (5, 1, 9000)]:
+                total = off + count + 3
+                acc = Guarded(count, np.float32)
+                ref = np.full(count, np.nan, np.float32)
+                for t in range(2):
+                    host = [gen.fill_host(gen.stream_key(1650 + p, gen.ROLE_GRAD, 0, t, q), 0, total, t16)
+                            for q in range(p)]
+                    mics.mics_reduce_scatter_accum_typed(acc.t, [upload(h) for h in host], off, count, t > 0, dtype)
+                    torch.cuda.synchronize()
+                    orc.reduce_scatter_accum_typed(ref, host, off, t > 0, code)
+                assert np.array_equal(acc.numpy().view(np.uint32), ref.view(np.uint32)), (name, p, off)
+                assert acc.guards_intact()
+        for p, k, numels, align in [(16, 8, [512 * 16, 16 * 40000, 16 * 8], 8), (8, 8, [1000, 77, 5000, 3], 1),
+                                    (3, 3, [30000, 24], 8)]:
+            lay = gen.coalesced_layout(numels, p, k, align=align)
+            total = lay.grad_off[-1]
+            segs = lay.reduce_segments(p - 1)
+            acc = Guarded(lay.shard_off[-1], np.float32)
+            ref = np.full(lay.shard_off[-1], np.nan, np.float32)
+            for t in range(2):
+                host = [gen.fill_host(gen.stream_key(1700, gen.ROLE_GRAD, 0, t, q), 0, total, tab) for q in range(p)]
+                mics.mics_reduce_scatter_accum_coalesced(acc.t, [upload(h) for h in host], segs, t > 0)
+                torch.cuda.synchronize()
+                orc.reduce_scatter_accum_coalesced(ref, host, segs, t > 0)
+            assert np.array_equal(acc.numpy().view(np.uint32), ref.view(np.uint32)), (p, numels)
+            assert acc.guards_intact()
+        atab = gen.normal_table(3e-2, "f32")
+        for r, count in [(8, 40003), (2, 9000), (3, 20001), (20, 5000)]:
+            host = [gen.fill_host(gen.stream_key(1750, gen.ROLE_ACC, c), 0, count, atab) for c in range(r)]
+            out = Guarded(count, np.float32)
+            mics.mics_replica_average(out.t, [upload(h) for h in host], count, 0.125)
+            torch.cuda.synchronize()
+            assert np.array_equal(out.numpy().view(np.uint32), orc.replica_average(host, 0.125).view(np.uint32))
+            assert out.guards_intact()
+    finally:
+        mics.mics_set_stream_threshold_bytes(0)

@@ -65,9 +65,8 @@ MUTANTS = [
 
 
 def run_pins(lib, files):
-    env = dict(os.environ, MICS_ORACLE_LIB=lib)
     return subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider", "-m", "not gpu",
-                           *files], cwd=ROOT, env=env, capture_output=True, text=True, timeout=300)
+                           "--oracle-lib", lib, *files], cwd=ROOT, capture_output=True, text=True, timeout=300)
 
 
 def build_variant(tmp_path, text):
