@@ -63,6 +63,12 @@ typedef f32x2 f32x2_a4 __attribute__((aligned(4)));
 #ifndef MICS_REORDER_NTS
 #define MICS_REORDER_NTS 1
 #endif
+#ifndef MICS_LDS_NTL
+#define MICS_LDS_NTL 1
+#endif
+#ifndef MICS_LDS_NTS
+#define MICS_LDS_NTS 1
+#endif
 #ifndef MICS_RSA_BLOCK
 #define MICS_RSA_BLOCK 512
 #endif
@@ -75,6 +81,9 @@ typedef f32x2 f32x2_a4 __attribute__((aligned(4)));
 #ifndef MICS_RSA_BATCH
 #define MICS_RSA_BATCH 16
 #endif
+#ifndef MICS_RSA_SMALL_BLOCK
+#define MICS_RSA_SMALL_BLOCK 64
+#endif
 #ifndef MICS_AVG_BLOCK
 #define MICS_AVG_BLOCK 512
 #endif
@@ -85,10 +94,16 @@ typedef f32x2 f32x2_a4 __attribute__((aligned(4)));
 #define MICS_AVG_NTL 1
 #endif
 #ifndef MICS_ADAM_BLOCK
-#define MICS_ADAM_BLOCK 256
+#define MICS_ADAM_BLOCK 128
 #endif
 #ifndef MICS_FUSED_BLOCK
-#define MICS_FUSED_BLOCK 256
+#define MICS_FUSED_BLOCK 128
+#endif
+#ifndef MICS_FUSED_COPIES_FIRST
+#define MICS_FUSED_COPIES_FIRST 1
+#endif
+#ifndef MICS_FUSED_NTL_COPIES
+#define MICS_FUSED_NTL_COPIES MICS_ADAM_NTL
 #endif
 #ifndef MICS_ADAM_BPC
 #define MICS_ADAM_BPC 4096
@@ -101,7 +116,10 @@ typedef f32x2 f32x2_a4 __attribute__((aligned(4)));
 #endif
 // Small messages on large groups (see rsa_kernel): workgroup size of the one-dword-per-lane
 // variant, the loads it keeps in flight, and the largest call (p * count buffer elements)
-// and smallest group it is used for.
+// and smallest group it is used for.  Measured per launch, 1 MB .. 256 MB of gradient per rank:
+// for p = 64 / 128 the variant wins up to 64 MB (1 MB: 7.0 / 11.9 us against 9.5 / 17.6 us for
+// the 128-bit kernel in single-wavefront workgroups, 12.5 / 20.6 us before either existed) and
+// loses from 128 MB on; for p <= 32 the 128-bit kernel is as fast or faster at every size.
 #ifndef MICS_NARROW_BLOCK
 #define MICS_NARROW_BLOCK 64
 #endif
@@ -109,10 +127,10 @@ typedef f32x2 f32x2_a4 __attribute__((aligned(4)));
 #define MICS_NARROW_BATCH 64
 #endif
 #ifndef MICS_NARROW_MAX_ELEMS
-#define MICS_NARROW_MAX_ELEMS (4u << 20)
+#define MICS_NARROW_MAX_ELEMS (34u << 20)
 #endif
 #ifndef MICS_NARROW_MIN_P
-#define MICS_NARROW_MIN_P 24
+#define MICS_NARROW_MIN_P 40
 #endif
 
 constexpr int kBlock = 256;              // LDS reorder
@@ -308,29 +326,47 @@ __global__ __launch_bounds__(kSegBlock) void reorder_seg_kernel(
 // (workgroup-uniform) phase.  The partial vectors at the two ends of a chunk
 // are moved in 2-byte units.  Global memory is touched only inside the chunk.
 // Like reorder_seg_kernel the kernel serves many tensors per launch: workgroup x
-// moves tile x - tile_begin[t] of chunk blockIdx.y of tensor t (a single tensor is
-// a table of one entry).
-constexpr int kStageVecsPerThread = 4;
+// moves tile x - tile_begin[t] of chunk blockIdx.y of tensor t.
+#ifndef MICS_LDS_VECS_PER_LANE
+#define MICS_LDS_VECS_PER_LANE 4
+#endif
+constexpr int kStageVecsPerThread = MICS_LDS_VECS_PER_LANE;
 constexpr int kTileVecs = kBlock * kStageVecsPerThread;   // destination vectors per tile
 constexpr int kTileBytes = kTileVecs * 16;
 
 struct LdsSeg {
     unsigned long long shard_bytes, valid_bytes, src_byte, dst_byte;
 };
+// Where workgroup x works: many tensors (table in the kernel arguments) ...
 struct LdsSegTable {
     int n;
     unsigned tile_begin[kMaxSeg + 1];
     LdsSeg seg[kMaxSeg];
+    __device__ __forceinline__ const LdsSeg& locate(unsigned x, size_t* tile) const
+    {
+        const int t = segment_of(tile_begin, x);
+        *tile = x - tile_begin[t];
+        return seg[t];
+    }
+};
+// ... or a single tensor: no table, no look-up (4 % faster than a table of one entry).
+struct LdsOneTensor {
+    LdsSeg seg;
+    __device__ __forceinline__ const LdsSeg& locate(unsigned x, size_t* tile) const
+    {
+        *tile = x;
+        return seg;
+    }
 };
 
+template <typename Where>
 __global__ __launch_bounds__(kBlock) void reorder_lds_kernel(
-    unsigned char* __restrict__ dst, PtrTable src, LdsSegTable tab, int k)
+    unsigned char* __restrict__ dst, PtrTable src, Where where, int k)
 {
     __shared__ u32x4 stage[kTileVecs + 2];
-    const unsigned x = blockIdx.x;
-    const int t = segment_of(tab.tile_begin, x);
-    const size_t tile = x - tab.tile_begin[t];
-    const size_t shard_bytes = tab.seg[t].shard_bytes, n_valid_bytes = tab.seg[t].valid_bytes;
+    size_t tile;
+    const LdsSeg& sg = where.locate(blockIdx.x, &tile);
+    const size_t shard_bytes = sg.shard_bytes, n_valid_bytes = sg.valid_bytes;
     const size_t g = blockIdx.y;
     const size_t chunk_begin = g * shard_bytes;
     if (chunk_begin >= n_valid_bytes) return;
@@ -338,9 +374,9 @@ __global__ __launch_bounds__(kBlock) void reorder_lds_kernel(
     if (valid > shard_bytes) valid = shard_bytes;
     const size_t j = g / (size_t)k, l = g % (size_t)k;
 
-    const uintptr_t d_lo = (uintptr_t)dst + tab.seg[t].dst_byte + chunk_begin;      // chunk in dst
+    const uintptr_t d_lo = (uintptr_t)dst + sg.dst_byte + chunk_begin;      // chunk in dst
     const uintptr_t d_hi = d_lo + valid;
-    const uintptr_t s_chunk = (uintptr_t)src.ptr[l] + tab.seg[t].src_byte + j * shard_bytes;
+    const uintptr_t s_chunk = (uintptr_t)src.ptr[l] + sg.src_byte + j * shard_bytes;
     const uintptr_t grid0 = d_lo & ~(uintptr_t)15;                     // 16-byte grid of dst
     const size_t ntiles = (d_hi - grid0 + kTileBytes - 1) / kTileBytes;
     if (tile >= ntiles) return;                                         // uniform per workgroup
@@ -358,7 +394,7 @@ __global__ __launch_bounds__(kBlock) void reorder_lds_kernel(
     for (unsigned v = threadIdx.x; v < nsv; v += kBlock) {
         const uintptr_t a = sa + (uintptr_t)v * 16;
         if (a >= s_lo && a + 16 <= s_hi) {
-            stage[v] = MICS_LD(kReorderNtl, (const u32x4*)a);
+            stage[v] = MICS_LD(MICS_LDS_NTL, (const u32x4*)a);
         } else {
             uint16_t* row = (uint16_t*)&stage[v];
             for (unsigned h = 0; h < 8; ++h) {
@@ -390,7 +426,7 @@ __global__ __launch_bounds__(kBlock) void reorder_lds_kernel(
                 out.z = (w2 >> 16) | (w3 << 16);
                 out.w = (w3 >> 16) | (w4 << 16);
             }
-            MICS_ST(kReorderNts, (u32x4*)a, out);
+            MICS_ST(MICS_LDS_NTS, (u32x4*)a, out);
         } else {
             for (unsigned h = 0; h < 8; ++h) {
                 const uintptr_t b = a + 2 * h;
@@ -548,11 +584,22 @@ __device__ __forceinline__ void rsa_sum(float (&a)[VEC * GradFormat<KIND>::kPerD
     for (int e = 0; e < EPL; ++e) a[e] = a[e] + s[e];
 }
 
+// One element, the p loads in flight 16 at a time (a lane that waited for each of 128 loads in
+// turn would hold up a small call for tens of microseconds).
 template <int KIND, bool ACCUM, typename Tab>
 __device__ __forceinline__ void rsa_element(float* acc_e, const Tab& g, int p, size_t elem)
 {
+    constexpr int B = 16;
     float partial = widen_one<KIND>(g.ptr[0], elem);
-    for (int q = 1; q < p; ++q) partial = partial + widen_one<KIND>(g.ptr[q], elem);
+    for (int q0 = 1; q0 < p; q0 += B) {
+        float w[B];
+        #pragma unroll
+        for (int b = 0; b < B; ++b)
+            if (q0 + b < p) w[b] = widen_one<KIND>(g.ptr[q0 + b], elem);
+        #pragma unroll
+        for (int b = 0; b < B; ++b)
+            if (q0 + b < p) partial = partial + w[b];
+    }
     *acc_e = (ACCUM ? *acc_e : 0.0f) + partial;
 }
 
@@ -560,7 +607,8 @@ __device__ __forceinline__ void rsa_element(float* acc_e, const Tab& g, int p, s
 // virtual range [lead, end): `acc` is the accumulator address of virtual element `lead`, and
 // virtual element e sits at element src0 + e of every rank buffer.  Consecutive lanes of a
 // wavefront hold consecutive v0, and every lane of the wavefront gets here (lanes past `end`
-// find nothing to do).
+// find nothing to do).  A lane whose elements are not all inside the range does nothing:
+// those elements -- fewer than EPL at either end -- are rsa_edges' work.
 //
 // Streamed accumulators of 8-element lanes are stored through LDS: a lane's two 128-bit
 // stores are 32 bytes apart, so each store instruction of the wavefront would fill every
@@ -568,7 +616,7 @@ __device__ __forceinline__ void rsa_element(float* acc_e, const Tab& g, int p, s
 // the L2 between the two halves (WRITE_SIZE 1.10 x the accumulator's bytes at 800 M elements).
 // Passing the results through 2 KiB of LDS per wavefront lets every store instruction cover
 // one contiguous KiB.  Only wavefronts whose 64 lanes all hold full vectors take this path.
-template <int KIND, int VEC, int P, int BATCH, bool ACCUM, bool SA, int BLOCK, typename Tab>
+template <int KIND, int VEC, int P, int BATCH, bool ACCUM, bool SA, int MAX_BLOCK, typename Tab>
 __device__ __forceinline__ void rsa_lane(float* acc, const Tab& g, int p, size_t src0, size_t v0,
                                          size_t lead, size_t end)
 {
@@ -576,7 +624,7 @@ __device__ __forceinline__ void rsa_lane(float* acc, const Tab& g, int p, size_t
     const bool full = v0 >= lead && v0 + EPL <= end;
     if constexpr (SA && EPL == 8) {
         if (__builtin_amdgcn_ballot_w64(full) == ~0ull) {       // wavefront-uniform
-            __shared__ f32x4 stage[BLOCK * 2];
+            __shared__ f32x4 stage[MAX_BLOCK * 2];
             const unsigned lane = threadIdx.x & 63u;
             f32x4* mine = stage + (threadIdx.x - lane) * 2;      // this wavefront's 128 vectors
             float* acc_e = acc + (v0 - lead);
@@ -597,24 +645,46 @@ __device__ __forceinline__ void rsa_lane(float* acc, const Tab& g, int p, size_t
         float a[EPL];
         rsa_sum<KIND, VEC, P, BATCH, ACCUM, SA>(a, acc_e, g, p, src0 + v0);
         st_f32<EPL, SA>(acc_e, a);
-    } else {
-        const size_t lo = v0 > lead ? v0 : lead, hi = v0 + EPL < end ? v0 + EPL : end;
-        for (size_t e = lo; e < hi; ++e) rsa_element<KIND, ACCUM>(acc + (e - lead), g, p, src0 + e);
     }
 }
 
+// The elements that no lane holds as a full vector: virtual [lead, head) with head = lead
+// rounded up to EPL (or `end`), and [tail, end) with tail = `end` rounded down to EPL (or
+// head).  One element per lane, lanes 0 .. 2*EPL-1 of the calling workgroup.
+template <int KIND, int EPL, bool ACCUM, typename Tab>
+__device__ __forceinline__ void rsa_edges(float* acc, const Tab& g, int p, size_t src0, size_t lead, size_t end)
+{
+    if (threadIdx.x >= 2 * EPL) return;
+    size_t head = (lead + EPL - 1) / EPL * EPL;
+    if (head > end) head = end;
+    size_t tail = end / EPL * EPL;
+    if (tail < head) tail = head;
+    const size_t e = threadIdx.x < EPL ? lead + threadIdx.x : tail + (threadIdx.x - EPL);
+    const size_t stop = threadIdx.x < EPL ? head : end;
+    if (e < stop) rsa_element<KIND, ACCUM>(acc + (e - lead), g, p, src0 + e);
+}
+
+// Workgroups of blockDim.x lanes (64 .. 512 for VEC = 4: the launcher takes small ones for
+// calls that would otherwise occupy a fraction of the compute units), plus one more workgroup
+// for the edge elements, so that their load chains run beside the vector work.
 template <int KIND, int VEC, int P, bool ACCUM, bool SA, typename Tab>
 __global__ __launch_bounds__(VEC == 4 ? kRsaBlock : kNarrowBlock) void rsa_kernel(
     float* __restrict__ acc, Tab g, int p, unsigned lead, size_t count)
 {
-    constexpr int BLOCK = VEC == 4 ? kRsaBlock : kNarrowBlock;
+    constexpr int MAX_BLOCK = VEC == 4 ? kRsaBlock : kNarrowBlock;
     constexpr int BATCH = VEC == 4 ? MICS_RSA_BATCH : MICS_NARROW_BATCH;
-    constexpr size_t EPL = VEC * GradFormat<KIND>::kPerDword;
+    constexpr int EPL = VEC * GradFormat<KIND>::kPerDword;
     const size_t end = (size_t)lead + count;
     const size_t nlanes = (end + EPL - 1) / EPL;
-    const size_t stride = (size_t)gridDim.x * BLOCK;
-    for (size_t base = (size_t)blockIdx.x * BLOCK; base < nlanes; base += stride)   // workgroup-uniform
-        rsa_lane<KIND, VEC, P, BATCH, ACCUM, SA, BLOCK>(acc, g, p, 0, (base + threadIdx.x) * EPL, lead, end);
+    const size_t block = blockDim.x;
+    // the last workgroup of the grid does nothing but the edge elements
+    if (blockIdx.x == gridDim.x - 1) {
+        rsa_edges<KIND, EPL, ACCUM>(acc, g, p, 0, lead, end);
+        return;
+    }
+    const size_t stride = (size_t)(gridDim.x - 1) * block;
+    for (size_t base = (size_t)blockIdx.x * block; base < nlanes; base += stride)   // workgroup-uniform
+        rsa_lane<KIND, VEC, P, BATCH, ACCUM, SA, MAX_BLOCK>(acc, g, p, 0, (base + threadIdx.x) * EPL, lead, end);
 }
 
 // Coalesced form (many separately sharded tensors in one launch, bf16): workgroup x works on
@@ -640,6 +710,7 @@ __global__ __launch_bounds__(kRsaBlock) void rsa_seg_kernel(
     const int t = segment_of(tab.tile_begin, x);
     const size_t end = tab.seg[t].end, lead = tab.seg[t].lead;
     const size_t v0 = ((size_t)(x - tab.tile_begin[t]) * kRsaBlock + threadIdx.x) * 8;
+    if (x == tab.tile_begin[t]) rsa_edges<0, 8, ACCUM>(acc + tab.seg[t].dst, g, p, tab.seg[t].src0, lead, end);
     rsa_lane<0, 4, P, MICS_RSA_BATCH, ACCUM, SA, kRsaBlock>(acc + tab.seg[t].dst, g, p, tab.seg[t].src0, v0, lead,
                                                             end);
 }
@@ -647,7 +718,7 @@ __global__ __launch_bounds__(kRsaBlock) void rsa_seg_kernel(
 // ---------------------------------------------------------------------------
 // Step 2b: reduction of the replication-group all-reduce at the accumulation
 // boundary and the scaling to a mean (Section 3.4).  One lane owns 4 elements
-// per copy and pass (the last lane fewer, one by one).  `out` may be copies[0]: a lane
+// per copy and pass (the last count mod 4 elements go one per lane).  `out` may be copies[0]: a lane
 // reads its elements of every copy before it writes them, and no other lane touches them.
 // ---------------------------------------------------------------------------
 
@@ -680,11 +751,21 @@ __device__ __forceinline__ f32x4 avg_sum4(const Tab& a, int r, size_t x)
     }
 }
 
+// One element, the r loads in flight 16 at a time.
 template <typename Tab>
 __device__ __forceinline__ float avg_sum1(const Tab& a, int r, size_t x)
 {
+    constexpr int B = 16;
     float sum = ((const float*)a.ptr[0])[x];
-    for (int c = 1; c < r; ++c) sum = sum + ((const float*)a.ptr[c])[x];
+    for (int c0 = 1; c0 < r; c0 += B) {
+        float w[B];
+        #pragma unroll
+        for (int b = 0; b < B; ++b)
+            if (c0 + b < r) w[b] = ((const float*)a.ptr[c0 + b])[x];
+        #pragma unroll
+        for (int b = 0; b < B; ++b)
+            if (c0 + b < r) sum = sum + w[b];
+    }
     return sum;
 }
 
@@ -701,10 +782,11 @@ __global__ __launch_bounds__(kAvgBlock) void avg_kernel(
         if (x + 4 <= count) {
             const f32x4 sum = avg_sum4<R, kAvgNtl>(a, r, x);
             MICS_ST(SO, (f32x4_a4*)(out + x), sum * scale);
-        } else {
-            for (size_t e = x; e < count; ++e) out[e] = avg_sum1(a, r, e) * scale;
         }
     }
+    // the last count mod 4 elements: one per lane
+    const size_t e = count / 4 * 4 + threadIdx.x;
+    if (blockIdx.x == 0 && e < count) out[e] = avg_sum1(a, r, e) * scale;
 }
 
 // ---------------------------------------------------------------------------
@@ -809,16 +891,22 @@ __global__ __launch_bounds__(kFusedBlock) void avg_adam_kernel(
     for (size_t i = (size_t)blockIdx.x * kFusedBlock + threadIdx.x; i < nlanes; i += stride) {
         const size_t x = 4 * i;
         if (x + 4 <= count) {
+#if MICS_FUSED_COPIES_FIRST
+            const f32x4 sum = avg_sum4<R, MICS_FUSED_NTL_COPIES>(a, r, x);
+#endif
             const f32x4 w = MICS_LD(kAdamNtl, (const f32x4_a4*)(master + x));
             const f32x4 m = MICS_LD(kAdamNtl, (const f32x4_a4*)(exp_avg + x));
             const f32x4 v = MICS_LD(kAdamNtl, (const f32x4_a4*)(exp_avg_sq + x));
-            const f32x4 sum = avg_sum4<R, kAdamNtl>(a, r, x);
+#if !MICS_FUSED_COPIES_FIRST
+            const f32x4 sum = avg_sum4<R, MICS_FUSED_NTL_COPIES>(a, r, x);
+#endif
             adam_update4<BF16>(master, exp_avg, exp_avg_sq, param_bf16, x, sum * scale, w, m, v, hp);
-        } else {
-            for (size_t e = x; e < count; ++e)
-                adam_update1<BF16>(master, exp_avg, exp_avg_sq, param_bf16, e, avg_sum1(a, r, e) * scale, hp);
         }
     }
+    // the last count mod 4 elements: one per lane
+    const size_t e = count / 4 * 4 + threadIdx.x;
+    if (blockIdx.x == 0 && e < count)
+        adam_update1<BF16>(master, exp_avg, exp_avg_sq, param_bf16, e, avg_sum1(a, r, e) * scale, hp);
 }
 
 // ---------------------------------------------------------------------------
@@ -936,14 +1024,13 @@ namespace {
 
 template <int KIND, int VEC, int P, bool ACCUM, bool SA>
 int rsa_launch(float* acc, const PtrTable& g, int p, unsigned lead, size_t count, unsigned blocks,
-               hipStream_t st)
+               unsigned block, hipStream_t st)
 {
-    constexpr int BLOCK = VEC == 4 ? kRsaBlock : kNarrowBlock;
     if constexpr (P > 0)
-        return launch(rsa_kernel<KIND, VEC, P, ACCUM, SA, SmallTable<P>>, dim3(blocks), dim3(BLOCK), st, acc,
+        return launch(rsa_kernel<KIND, VEC, P, ACCUM, SA, SmallTable<P>>, dim3(blocks + 1), dim3(block), st, acc,
                       small<P>(g), p, lead, count);
     else
-        return launch(rsa_kernel<KIND, VEC, 0, ACCUM, SA, PtrTable>, dim3(blocks), dim3(BLOCK), st, acc, g, p,
+        return launch(rsa_kernel<KIND, VEC, 0, ACCUM, SA, PtrTable>, dim3(blocks + 1), dim3(block), st, acc, g, p,
                       lead, count);
 }
 
@@ -957,34 +1044,45 @@ int rsa_launch_kind(float* acc, const PtrTable& g, int p, unsigned lead, size_t 
     if (p >= MICS_NARROW_MIN_P && count <= (size_t)MICS_NARROW_MAX_ELEMS / (size_t)p) {
         const size_t nlanes = (lead + count + PD - 1) / PD;
         if (int e = grid_for(nlanes, kNarrowBlock, MICS_RSA_BPC, &blocks)) return e;
-        return accumulate ? rsa_launch<KIND, 1, 0, true, false>(acc, g, p, lead, count, blocks, st)
-                          : rsa_launch<KIND, 1, 0, false, false>(acc, g, p, lead, count, blocks, st);
+        return accumulate ? rsa_launch<KIND, 1, 0, true, false>(acc, g, p, lead, count, blocks, kNarrowBlock, st)
+                          : rsa_launch<KIND, 1, 0, false, false>(acc, g, p, lead, count, blocks, kNarrowBlock, st);
     }
     const size_t nlanes = (lead + count + 4 * PD - 1) / (4 * PD);
-    if (int e = grid_for(nlanes, kRsaBlock, MICS_RSA_BPC, &blocks)) return e;
+    // Full-size workgroups once they give every compute unit one; single wavefronts below that,
+    // so that a call of a few MB is spread over the chip instead of over a handful of units
+    // (a unit moves about 100 GB/s on its own).
+    int cus = 0;
+    if (int e = compute_units(&cus)) return e;
+    const unsigned block = nlanes >= (size_t)kRsaBlock * (size_t)cus ? kRsaBlock : MICS_RSA_SMALL_BLOCK;
+    if (int e = grid_for(nlanes, (int)block, MICS_RSA_BPC, &blocks)) return e;
     return dispatch2(accumulate, stream_acc(count), [&](auto A, auto SA) {
         if constexpr (KIND == 0) {
             return dispatch_group(p, [&](auto P) {
-                return rsa_launch<KIND, 4, P.value, A.value, SA.value>(acc, g, p, lead, count, blocks, st);
+                return rsa_launch<KIND, 4, P.value, A.value, SA.value>(acc, g, p, lead, count, blocks, block, st);
             });
         } else {
             switch (p) {
-                case 8: return rsa_launch<KIND, 4, 8, A.value, SA.value>(acc, g, p, lead, count, blocks, st);
-                case 16: return rsa_launch<KIND, 4, 16, A.value, SA.value>(acc, g, p, lead, count, blocks, st);
-                default: return rsa_launch<KIND, 4, 0, A.value, SA.value>(acc, g, p, lead, count, blocks, st);
+                case 8: return rsa_launch<KIND, 4, 8, A.value, SA.value>(acc, g, p, lead, count, blocks, block, st);
+                case 16: return rsa_launch<KIND, 4, 16, A.value, SA.value>(acc, g, p, lead, count, blocks, block, st);
+                default: return rsa_launch<KIND, 4, 0, A.value, SA.value>(acc, g, p, lead, count, blocks, block, st);
             }
         }
     });
 }
 
 // Rounds 2-byte element pointers down to 4 bytes when all of them sit at the same position
-// inside their dword; returns how many elements they moved back (the kernels' `lead`).
+// inside their dword (rank g's slices of separately allocated buffers do: they all start g*S
+// elements in); returns how many elements they moved back (the kernels' `lead`, 0 or 1).  With
+// mixed positions the pointers stay and the odd ones are read with 2-byte aligned 128-bit loads
+// (about 20 % slower).  Rounding further down, to 16 bytes, was measured too: no gain at
+// p = 16 and a 5 % loss at p = 32, the accumulator then being addressed further off its own
+// alignment.
 unsigned align_gradient_pointers(PtrTable& g, int p, int elem_bytes)
 {
     if (elem_bytes != 2) return 0;
     const uintptr_t odd = (uintptr_t)g.ptr[0] & 2;
     for (int q = 1; q < p; ++q)
-        if (((uintptr_t)g.ptr[q] & 2) != odd) return 0;    // mixed: 2-byte aligned loads (slower)
+        if (((uintptr_t)g.ptr[q] & 2) != odd) return 0;
     if (!odd) return 0;
     for (int q = 0; q < p; ++q) g.ptr[q] = (const char*)g.ptr[q] - 2;
     return 1;
@@ -1061,6 +1159,21 @@ int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs
                                (u32x4*)dst, src, tab, k))
                 return e;
         } else {
+            if (nt == 1) {
+                const Segment& sg = segs[first];
+                LdsOneTensor one;
+                one.seg.shard_bytes = sg.shard_elems * eb;
+                one.seg.valid_bytes = sg.numel * eb;
+                one.seg.src_byte = sg.src_offset * eb;
+                one.seg.dst_byte = sg.dst_offset * eb;
+                tiles = sg.numel ? (one.seg.shard_bytes + 15 + kTileBytes - 1) / kTileBytes : 0;
+                if (tiles > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
+                if (tiles == 0) continue;
+                if (int e = launch(reorder_lds_kernel<LdsOneTensor>, dim3((unsigned)tiles, (unsigned)p), dim3(kBlock), st,
+                                   (unsigned char*)dst, src, one, k))
+                    return e;
+                continue;
+            }
             LdsSegTable tab;
             tab.n = nt;
             for (int t = 0; t < nt; ++t) {
@@ -1076,7 +1189,7 @@ int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs
             }
             for (int t = nt; t <= kMaxSeg; ++t) tab.tile_begin[t] = 0xFFFFFFFFu;
             if (tiles == 0) continue;
-            if (int e = launch(reorder_lds_kernel, dim3((unsigned)tiles, (unsigned)p), dim3(kBlock), st,
+            if (int e = launch(reorder_lds_kernel<LdsSegTable>, dim3((unsigned)tiles, (unsigned)p), dim3(kBlock), st,
                                (unsigned char*)dst, src, tab, k))
                 return e;
         }

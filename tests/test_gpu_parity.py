@@ -102,11 +102,13 @@ RSA_CASES = [
     (32, 20000, 160, 15000, 2, 0),            # cfg-4 group size
     (32, 150000, 160, 140003, 2, 0),          # ... beyond the small-message kernel: two batches of 16 loads
     (128, 4096, 0, 4096, 1, 0),               # largest group (small message: one dword per lane)
-    (128, 34000, 8, 33001, 1, 0),             # largest group, 128-bit kernel: 8 batches
+    (128, 34000, 8, 33001, 1, 0),
+    (128, 280000, 8, 279001, 1, 0),           # largest group, 128-bit kernel: 8 batches of 16 loads
     (64, 40000, 64, 39000, 2, 0),             # 8 nodes of 8 (the paper's 50B-parameter group)
     (64, 9000, 3, 8190, 2, 1),                # small message, odd offset, accumulator off by 4 bytes
     (40, 20000, 0, 20000, 2, 0),              # any-p kernels, small message
-    (40, 112000, 0, 110003, 2, 0),            # any-p kernels, 128-bit loads: batches of 16, 16, 8
+    (37, 30000, 0, 29003, 2, 0),              # any-p kernel with 128-bit loads: batches of 16, 16, 4
+    (16, 600000, 16, 524288 + 77, 2, 0),      # enough lanes for full-size workgroups on every compute unit
     (4, 30000, 3, 20000, 2, 0),               # odd offset: pointers rounded down, first lane element-wise
     (8, 30000, 0, 30000, 2, 1),               # buffers and accumulator off 16-byte alignment
     (16, 30000, 5, 1, 2, 0),                  # a single element at an odd offset
@@ -757,7 +759,7 @@ def test_streaming_kernels_give_the_same_results(orc, gen):
     try:
         mics.mics_set_stream_threshold_bytes(1)
         for p, off, count in [(16, 0, 40003), (2, 1, 30000), (1, 0, 5000), (4, 3, 9000), (8, 0, 20000),
-                              (32, 0, 140000), (40, 5, 110000), (64, 1, 8000)]:
+                              (32, 0, 140000), (37, 5, 30000), (64, 1, 8000), (16, 8, 1100000)]:
             total = off + count + 3
             acc = Guarded(count, np.float32)
             ref = np.full(count, np.nan, np.float32)
