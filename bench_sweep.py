@@ -3,7 +3,7 @@
 
 The paper's collective micro-benchmark (Section 5.2) sweeps message sizes up to 256 MB, because a
 single parameter fetch usually gathers less than that.  This script times the on-device halves of
-those collectives over the same range, 1 MB .. 256 MB, for partition groups of 16, 64 and 128
+those collectives over the same range, 1 MB .. 256 MB, for partition groups of 16, 32, 64 and 128
 ranks (k = 8 devices per node): how the kernels behave on small messages and where the launch
 latency floor lies.
 
@@ -29,7 +29,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--reps", type=int, default=30)
     ap.add_argument("--sizes-mb", default="1,2,4,8,16,32,64,128,256")
-    ap.add_argument("--groups", default="16,64,128")
+    ap.add_argument("--groups", default="16,32,64,128")
     ap.add_argument("--footprint-mb", type=int, default=1024,
                     help="rotate through at least this many MB of distinct buffers per measurement")
     args = ap.parse_args()

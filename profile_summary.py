@@ -102,6 +102,8 @@ def main():
     ap.add_argument("--bench-args", default="")
     ap.add_argument("--out", required=True)
     ap.add_argument("--no-traffic-file", action="store_true")
+    ap.add_argument("--append", action="store_true", help="append to --out instead of replacing it")
+    ap.add_argument("--title", default="", help="heading for this run (variants collected in one file)")
     args = ap.parse_args()
 
     import synth
@@ -110,7 +112,8 @@ def main():
     count = args.count or (cfg.N_pad if args.view == "group" else cfg.S)
     pb = 2
     sha = hashlib.sha256(open(KERNEL_SOURCE, "rb").read()).hexdigest()[:16]
-    out = [f"# rocprofv3 summary: libmics kernels, workload {cfg.name} (p={cfg.p}, k={cfg.k}, r={cfg.r}, "
+    out = [(f"\n---\n\n## {args.title}\n\n" if args.title else "") +
+           f"# rocprofv3 summary: libmics kernels, workload {cfg.name} (p={cfg.p}, k={cfg.k}, r={cfg.r}, "
            f"s={cfg.s}), {args.view} view ({count} elements per reduce/average/Adam call), one MI355X\n",
            f"Kernel source: `paper_2205_00119_amd/csrc/kernels.hip`, SHA-256 `{sha}`.\n",
            "Commands (from /tmp on the GPU box, `R` = repository root; each in a run of its own), then "
@@ -160,30 +163,32 @@ def main():
 
     # ---- counters -------------------------------------------------------------------------------
     if have_pmc:
-        rows = {}
+        rows, cal = {}, {}
         for tag in ("fetch", "write"):
-            for row in csv.DictReader(open(one(os.path.join(args.dir, tag, "**", "*counter_collection.csv")))):
+            recs = list(csv.DictReader(open(one(os.path.join(args.dir, tag, "**", "*counter_collection.csv")))))
+            recs.sort(key=lambda row: int(row["Dispatch_Id"]))
+            for row in recs:
                 n = short_name(row["Kernel_Name"])
                 if algorithmic_bytes(n, cfg, count, N, pb) is None:
                     continue
+                if tag not in cal and n.startswith("reorder_"):
+                    cal[tag] = (n, float(row["Counter_Value"]))      # the calibration copy comes first
+                    continue
                 rows.setdefault(n, {}).setdefault(tag, []).append(float(row["Counter_Value"]))
-        cal = rows.get("reorder_vec_kernel")
-        if not cal:
-            raise SystemExit("no calibration copy (reorder_vec_kernel) in the counter runs")
+        if len(cal) != 2:
+            raise SystemExit("no calibration copy (first reorder dispatch) in the counter runs")
         cal_kib = pb * N / KIB
-        ff, fw = cal_kib / cal["fetch"][0], cal_kib / cal["write"][0]
+        ff, fw = cal_kib / cal["fetch"][1], cal_kib / cal["write"][1]
         out.append("## HBM traffic per dispatch (`--pmc FETCH_SIZE`, `--pmc WRITE_SIZE`; counters in KiB)\n")
-        out.append(f"Calibration: the first `reorder_vec_kernel` dispatch of these two runs is a plain copy (p = k = 1) of "
-                   f"N = {N} bf16 = {cal_kib:.0f} KiB read and as much written. FETCH_SIZE reads {cal['fetch'][0]:.1f} "
-                   f"and WRITE_SIZE reads {cal['write'][0]:.1f} for it, so the scale factors are **{ff:.4f}** (fetch) "
-                   f"and **{fw:.4f}** (write).\n")
+        out.append(f"Calibration: the first reorder dispatch of these two runs (`{cal['fetch'][0]}`) is a plain copy "
+                   f"(p = k = 1) of N = {N} bf16 = {cal_kib:.0f} KiB read and as much written. FETCH_SIZE reads "
+                   f"{cal['fetch'][1]:.1f} and WRITE_SIZE reads {cal['write'][1]:.1f} for it, so the scale factors are "
+                   f"**{ff:.4f}** (fetch) and **{fw:.4f}** (write).\n")
         out.append("| kernel | dispatches | FETCH_SIZE avg | x factor = KiB read | WRITE_SIZE avg | x factor = KiB written | traffic bytes | algorithmic bytes | ratio |")
         out.append("|---|---|---|---|---|---|---|---|---|")
         traffic = {}
         for n, v in sorted(rows.items()):
             f, w = v.get("fetch", []), v.get("write", [])
-            if n == "reorder_vec_kernel":
-                f, w = f[1:], w[1:]
             if not f or not w:
                 continue
             fa, wa = sum(f) / len(f), sum(w) / len(w)
@@ -213,7 +218,7 @@ def main():
                             "# workload view variant sha256-16(kernels.hip) bytes fetch_factor write_factor summary"]
                 keep.append(f"{cfg.name} {args.view} {args.variant} {sha} {per_launch:.0f} {ff:.4f} {fw:.4f} {args.out}")
                 open(TRAFFIC_FILE, "w").write("\n".join(keep) + "\n")
-    open(args.out, "w").write("\n".join(out) + "\n")
+    open(args.out, "a" if args.append else "w").write("\n".join(out) + "\n")
     print("\n".join(out))
 
 
