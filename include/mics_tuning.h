@@ -30,6 +30,21 @@ int mics_set_blocks_per_cu(int blocks_per_cu);
  */
 int mics_set_stream_threshold_bytes(size_t bytes);
 
+/*
+ * Launch shape of a kernel family for later calls: lanes per workgroup (64, 128, 256 or 512) and
+ * the most wavefronts a compute unit may hold at a time (1 .. 32; 32 = as many as fit); 0 for
+ * either restores the built-in choice, which depends on the size of the call and on the
+ * alignment of its buffers.  Streaming kernels on an MI355X run fastest in single-wavefront
+ * workgroups with 8 to 16 wavefronts per compute unit; this knob is how that was measured.
+ * Returns MICS_OK or MICS_ERR_INVALID_ARG.
+ */
+#define MICS_KERNELS_REORDER 0   /* mics_hier_gather_reorder (16-byte aligned geometry)       */
+#define MICS_KERNELS_REDUCE  1   /* mics_reduce_scatter_accum, _typed, _coalesced             */
+#define MICS_KERNELS_AVERAGE 2   /* mics_replica_average                                      */
+#define MICS_KERNELS_ADAM    3   /* mics_adam_shard                                           */
+#define MICS_KERNELS_FUSED   4   /* mics_replica_average_adam_shard                           */
+int mics_set_launch_shape(int kernel_family, int lanes, int waves_per_cu);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ MICS_MAX_GROUP = 128
 
 EXPORTS = (
     "mics_version", "mics_last_error", "mics_shard_elems", "mics_set_blocks_per_cu",
-    "mics_set_stream_threshold_bytes",
+    "mics_set_stream_threshold_bytes", "mics_set_launch_shape",
     "mics_hier_gather_reorder", "mics_reduce_scatter_accum", "mics_replica_average",
     "mics_adam_shard", "mics_hier_gather_reorder_coalesced", "mics_reduce_scatter_accum_coalesced",
     "mics_replica_average_adam_shard", "mics_reduce_scatter_accum_typed",
@@ -60,6 +60,8 @@ lib.mics_set_blocks_per_cu.argtypes = [_i]
 lib.mics_set_blocks_per_cu.restype = _i
 lib.mics_set_stream_threshold_bytes.argtypes = [_sz]
 lib.mics_set_stream_threshold_bytes.restype = _i
+lib.mics_set_launch_shape.argtypes = [_i, _i, _i]
+lib.mics_set_launch_shape.restype = _i
 lib.mics_hier_gather_reorder.argtypes = [_vp, _vp, _sz, _sz, _i, _i, _i, _vp]
 lib.mics_hier_gather_reorder.restype = _i
 lib.mics_reduce_scatter_accum.argtypes = [_vp, _vp, _sz, _sz, _i, _i, _vp]
@@ -145,6 +147,13 @@ def mics_set_blocks_per_cu(blocks_per_cu: int) -> None:
 
 def mics_set_stream_threshold_bytes(nbytes: int) -> None:
     _check(lib.mics_set_stream_threshold_bytes(nbytes))
+
+
+MICS_KERNELS_REORDER, MICS_KERNELS_REDUCE, MICS_KERNELS_AVERAGE, MICS_KERNELS_ADAM, MICS_KERNELS_FUSED = range(5)
+
+
+def mics_set_launch_shape(kernel_family: int, lanes: int = 0, waves_per_cu: int = 0) -> None:
+    _check(lib.mics_set_launch_shape(kernel_family, lanes, waves_per_cu))
 
 
 def mics_hier_gather_reorder(dst_flat, stage1_bufs: Sequence, n_valid: int, shard_elems: int,

@@ -107,6 +107,20 @@ int mics_set_stream_threshold_bytes(size_t bytes)
     return MICS_OK;
 }
 
+int mics_set_launch_shape(int kernel_family, int lanes, int waves_per_cu)
+{
+    const char* fn = "mics_set_launch_shape";
+    if (kernel_family < 0 || kernel_family >= mics::kFamilies)
+        return fail(MICS_ERR_INVALID_ARG, "%s: kernel_family = %d not in [0, %d]", fn, kernel_family,
+                    mics::kFamilies - 1);
+    if (lanes != 0 && lanes != 64 && lanes != 128 && lanes != 256 && lanes != 512)
+        return fail(MICS_ERR_INVALID_ARG, "%s: lanes = %d is not 0, 64, 128, 256 or 512", fn, lanes);
+    if (waves_per_cu < 0 || waves_per_cu > 32)
+        return fail(MICS_ERR_INVALID_ARG, "%s: waves_per_cu = %d not in [0, 32]", fn, waves_per_cu);
+    mics::set_launch_shape(kernel_family, lanes, waves_per_cu);
+    return MICS_OK;
+}
+
 int mics_hier_gather_reorder(void* dst_flat, const void* const* stage1_bufs,
                              size_t n_valid, size_t shard_elems, int p, int k,
                              int elem_bytes, void* stream)

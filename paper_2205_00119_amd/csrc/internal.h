@@ -65,9 +65,13 @@ int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs
 int launch_reduce_coalesced(float* acc, const PtrTable& grads, const Segment* segs, int n, int p,
                             bool accumulate, void* stream);
 
+// Kernel families whose launch shape can be set (mics_tuning.h).
+enum { kFamReorder = 0, kFamReduce = 1, kFamAverage = 2, kFamAdam = 3, kFamFused = 4, kFamilies = 5 };
+
 // 0 = built-in choice.
 void set_blocks_per_cu(int n);
 void set_stream_threshold_bytes(size_t n);
+void set_launch_shape(int family, int lanes, int waves_per_cu);
 
 const char* hip_error_text(int err);
 

@@ -52,7 +52,7 @@ typedef f32x2 f32x2_a4 __attribute__((aligned(4)));
 // workgroups per compute unit (the grid covers the data with one pass per lane unless the
 // cap is reached; lanes stride over the rest), *_NTL / *_NTS = non-temporal loads / stores.
 #ifndef MICS_REORDER_BLOCK
-#define MICS_REORDER_BLOCK 256
+#define MICS_REORDER_BLOCK 64
 #endif
 #ifndef MICS_REORDER_BPC
 #define MICS_REORDER_BPC 4096
@@ -70,7 +70,16 @@ typedef f32x2 f32x2_a4 __attribute__((aligned(4)));
 #define MICS_LDS_NTS 1
 #endif
 #ifndef MICS_RSA_BLOCK
-#define MICS_RSA_BLOCK 512
+#define MICS_RSA_BLOCK 64
+#endif
+#ifndef MICS_RSA_UNALIGNED_BLOCK
+#define MICS_RSA_UNALIGNED_BLOCK 512     // accumulator or gradients off 16 bytes: 6070 against 5740 with 64
+#endif
+#ifndef MICS_RSA_WAVES
+#define MICS_RSA_WAVES 10
+#endif
+#ifndef MICS_RSA_WAVES_STREAMED
+#define MICS_RSA_WAVES_STREAMED 4
 #endif
 #ifndef MICS_RSA_BPC
 #define MICS_RSA_BPC 4096
@@ -81,11 +90,14 @@ typedef f32x2 f32x2_a4 __attribute__((aligned(4)));
 #ifndef MICS_RSA_BATCH
 #define MICS_RSA_BATCH 16
 #endif
-#ifndef MICS_RSA_SMALL_BLOCK
-#define MICS_RSA_SMALL_BLOCK 64
-#endif
 #ifndef MICS_AVG_BLOCK
-#define MICS_AVG_BLOCK 512
+#define MICS_AVG_BLOCK 64
+#endif
+#ifndef MICS_AVG_WAVES
+#define MICS_AVG_WAVES 12
+#endif
+#ifndef MICS_AVG_WAVES_STREAMED
+#define MICS_AVG_WAVES_STREAMED 12
 #endif
 #ifndef MICS_AVG_BPC
 #define MICS_AVG_BPC 4096
@@ -94,10 +106,19 @@ typedef f32x2 f32x2_a4 __attribute__((aligned(4)));
 #define MICS_AVG_NTL 1
 #endif
 #ifndef MICS_ADAM_BLOCK
-#define MICS_ADAM_BLOCK 128
+#define MICS_ADAM_BLOCK 64
+#endif
+#ifndef MICS_ADAM_WAVES
+#define MICS_ADAM_WAVES 12
+#endif
+#ifndef MICS_ADAM_WAVES_STREAMED
+#define MICS_ADAM_WAVES_STREAMED 10
 #endif
 #ifndef MICS_FUSED_BLOCK
-#define MICS_FUSED_BLOCK 128
+#define MICS_FUSED_BLOCK 64
+#endif
+#ifndef MICS_FUSED_WAVES
+#define MICS_FUSED_WAVES 6
 #endif
 #ifndef MICS_FUSED_COPIES_FIRST
 #define MICS_FUSED_COPIES_FIRST 1
@@ -134,12 +155,8 @@ typedef f32x2 f32x2_a4 __attribute__((aligned(4)));
 #endif
 
 constexpr int kBlock = 256;              // LDS reorder
-constexpr int kReorderBlock = MICS_REORDER_BLOCK;
-constexpr int kRsaBlock = MICS_RSA_BLOCK;
+constexpr int kMaxBlock = 512;           // most lanes per workgroup of the element-wise kernels
 constexpr int kNarrowBlock = MICS_NARROW_BLOCK;
-constexpr int kAvgBlock = MICS_AVG_BLOCK;
-constexpr int kAdamBlock = MICS_ADAM_BLOCK;
-constexpr int kFusedBlock = MICS_FUSED_BLOCK;
 constexpr bool kReorderNtl = MICS_REORDER_NTL, kReorderNts = MICS_REORDER_NTS;
 constexpr bool kRsaNtl = MICS_RSA_NTL;   // gradient loads; the accumulator's hint is chosen per launch
 constexpr bool kAvgNtl = MICS_AVG_NTL;   // input loads; the output's hint is chosen per launch
@@ -217,7 +234,7 @@ __device__ __forceinline__ uint16_t bf16_single(float a)
 // ---------------------------------------------------------------------------
 
 // All addresses and the shard size are multiples of 16 bytes: a remapped copy.
-__global__ __launch_bounds__(kReorderBlock) void reorder_vec_kernel(
+__global__ __launch_bounds__(kMaxBlock) void reorder_vec_kernel(
     u32x4* __restrict__ dst, PtrTable src, size_t shard_vecs, size_t n_valid_bytes, int k)
 {
     const size_t g = blockIdx.y;
@@ -234,8 +251,8 @@ __global__ __launch_bounds__(kReorderBlock) void reorder_vec_kernel(
     // in flight cover one compact, advancing window of the source and of the destination; a
     // lane that strides far ahead (several loads a grid stride apart) measurably lowers the
     // achieved bandwidth, for loads and even more for stores.
-    const size_t stride = (size_t)gridDim.x * kReorderBlock;
-    for (size_t i = (size_t)blockIdx.x * kReorderBlock + threadIdx.x; i < nfull; i += stride)
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nfull; i += stride)
         MICS_ST(kReorderNts, d + i, MICS_LD(kReorderNtl, s + i));
 
     // ragged end of the logical buffer: fewer than 16 valid bytes remain
@@ -616,7 +633,7 @@ __device__ __forceinline__ void rsa_element(float* acc_e, const Tab& g, int p, s
 // the L2 between the two halves (WRITE_SIZE 1.10 x the accumulator's bytes at 800 M elements).
 // Passing the results through 2 KiB of LDS per wavefront lets every store instruction cover
 // one contiguous KiB.  Only wavefronts whose 64 lanes all hold full vectors take this path.
-template <int KIND, int VEC, int P, int BATCH, bool ACCUM, bool SA, int MAX_BLOCK, typename Tab>
+template <int KIND, int VEC, int P, int BATCH, bool ACCUM, bool SA, typename Tab>
 __device__ __forceinline__ void rsa_lane(float* acc, const Tab& g, int p, size_t src0, size_t v0,
                                          size_t lead, size_t end)
 {
@@ -624,7 +641,7 @@ __device__ __forceinline__ void rsa_lane(float* acc, const Tab& g, int p, size_t
     const bool full = v0 >= lead && v0 + EPL <= end;
     if constexpr (SA && EPL == 8) {
         if (__builtin_amdgcn_ballot_w64(full) == ~0ull) {       // wavefront-uniform
-            __shared__ f32x4 stage[MAX_BLOCK * 2];
+            extern __shared__ f32x4 stage[];                     // blockDim.x * 2 vectors (launcher)
             const unsigned lane = threadIdx.x & 63u;
             f32x4* mine = stage + (threadIdx.x - lane) * 2;      // this wavefront's 128 vectors
             float* acc_e = acc + (v0 - lead);
@@ -668,10 +685,9 @@ __device__ __forceinline__ void rsa_edges(float* acc, const Tab& g, int p, size_
 // calls that would otherwise occupy a fraction of the compute units), plus one more workgroup
 // for the edge elements, so that their load chains run beside the vector work.
 template <int KIND, int VEC, int P, bool ACCUM, bool SA, typename Tab>
-__global__ __launch_bounds__(VEC == 4 ? kRsaBlock : kNarrowBlock) void rsa_kernel(
+__global__ __launch_bounds__(VEC == 4 ? kMaxBlock : kNarrowBlock) void rsa_kernel(
     float* __restrict__ acc, Tab g, int p, unsigned lead, size_t count)
 {
-    constexpr int MAX_BLOCK = VEC == 4 ? kRsaBlock : kNarrowBlock;
     constexpr int BATCH = VEC == 4 ? MICS_RSA_BATCH : MICS_NARROW_BATCH;
     constexpr int EPL = VEC * GradFormat<KIND>::kPerDword;
     const size_t end = (size_t)lead + count;
@@ -684,7 +700,7 @@ __global__ __launch_bounds__(VEC == 4 ? kRsaBlock : kNarrowBlock) void rsa_kerne
     }
     const size_t stride = (size_t)(gridDim.x - 1) * block;
     for (size_t base = (size_t)blockIdx.x * block; base < nlanes; base += stride)   // workgroup-uniform
-        rsa_lane<KIND, VEC, P, BATCH, ACCUM, SA, MAX_BLOCK>(acc, g, p, 0, (base + threadIdx.x) * EPL, lead, end);
+        rsa_lane<KIND, VEC, P, BATCH, ACCUM, SA>(acc, g, p, 0, (base + threadIdx.x) * EPL, lead, end);
 }
 
 // Coalesced form (many separately sharded tensors in one launch, bf16): workgroup x works on
@@ -703,16 +719,15 @@ struct ReduceSegTable {
 };
 
 template <int P, bool ACCUM, bool SA, typename Tab>
-__global__ __launch_bounds__(kRsaBlock) void rsa_seg_kernel(
+__global__ __launch_bounds__(kMaxBlock) void rsa_seg_kernel(
     float* __restrict__ acc, Tab g, int p, ReduceSegTable tab)
 {
     const unsigned x = blockIdx.x;
     const int t = segment_of(tab.tile_begin, x);
     const size_t end = tab.seg[t].end, lead = tab.seg[t].lead;
-    const size_t v0 = ((size_t)(x - tab.tile_begin[t]) * kRsaBlock + threadIdx.x) * 8;
+    const size_t v0 = ((size_t)(x - tab.tile_begin[t]) * blockDim.x + threadIdx.x) * 8;
     if (x == tab.tile_begin[t]) rsa_edges<0, 8, ACCUM>(acc + tab.seg[t].dst, g, p, tab.seg[t].src0, lead, end);
-    rsa_lane<0, 4, P, MICS_RSA_BATCH, ACCUM, SA, kRsaBlock>(acc + tab.seg[t].dst, g, p, tab.seg[t].src0, v0, lead,
-                                                            end);
+    rsa_lane<0, 4, P, MICS_RSA_BATCH, ACCUM, SA>(acc + tab.seg[t].dst, g, p, tab.seg[t].src0, v0, lead, end);
 }
 
 // ---------------------------------------------------------------------------
@@ -772,12 +787,12 @@ __device__ __forceinline__ float avg_sum1(const Tab& a, int r, size_t x)
 // SO ("stream the output"): non-temporal stores for results too large for the Infinity Cache,
 // as for the accumulator of the reduce kernels.
 template <int R, bool SO, typename Tab>
-__global__ __launch_bounds__(kAvgBlock) void avg_kernel(
+__global__ __launch_bounds__(kMaxBlock) void avg_kernel(
     float* out, Tab a, int r, float scale, size_t count)
 {
     const size_t nlanes = (count + 3) / 4;
-    const size_t stride = (size_t)gridDim.x * kAvgBlock;
-    for (size_t i = (size_t)blockIdx.x * kAvgBlock + threadIdx.x; i < nlanes; i += stride) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nlanes; i += stride) {
         const size_t x = 4 * i;
         if (x + 4 <= count) {
             const f32x4 sum = avg_sum4<R, kAvgNtl>(a, r, x);
@@ -855,13 +870,13 @@ __device__ __forceinline__ void adam_update1(float* master, float* exp_avg, floa
 // anywhere on an element boundary -- for instance inside the stage-1 buffer of the next
 // parameter gather, at T_l + j*S.
 template <bool BF16>
-__global__ __launch_bounds__(kAdamBlock) void adam_kernel(
+__global__ __launch_bounds__(kMaxBlock) void adam_kernel(
     float* __restrict__ master, float* __restrict__ exp_avg, float* __restrict__ exp_avg_sq,
     uint16_t* __restrict__ param_bf16, const float* __restrict__ grad, size_t count, AdamScalars hp)
 {
     const size_t nlanes = (count + 3) / 4;
-    const size_t stride = (size_t)gridDim.x * kAdamBlock;
-    for (size_t i = (size_t)blockIdx.x * kAdamBlock + threadIdx.x; i < nlanes; i += stride) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nlanes; i += stride) {
         const size_t x = 4 * i;
         if (x + 4 <= count) {
             const f32x4 g = MICS_LD(kAdamNtl, (const f32x4_a4*)(grad + x));
@@ -882,13 +897,13 @@ __global__ __launch_bounds__(kAdamBlock) void adam_kernel(
 // 4r + 12 bytes read and 14 written per element instead of (4r + 4) + 30.  R > 0: r = R at
 // compile time; R == 0: any r in batches of 16 loads.
 template <int R, bool BF16, typename Tab>
-__global__ __launch_bounds__(kFusedBlock) void avg_adam_kernel(
+__global__ __launch_bounds__(kMaxBlock) void avg_adam_kernel(
     float* __restrict__ master, float* __restrict__ exp_avg, float* __restrict__ exp_avg_sq,
     uint16_t* __restrict__ param_bf16, Tab a, int r, float scale, size_t count, AdamScalars hp)
 {
     const size_t nlanes = (count + 3) / 4;
-    const size_t stride = (size_t)gridDim.x * kFusedBlock;
-    for (size_t i = (size_t)blockIdx.x * kFusedBlock + threadIdx.x; i < nlanes; i += stride) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nlanes; i += stride) {
         const size_t x = 4 * i;
         if (x + 4 <= count) {
 #if MICS_FUSED_COPIES_FIRST
@@ -955,14 +970,72 @@ int grid_for(size_t items, int block, int bpc, unsigned* blocks)
 
 template <typename T> struct same_type { typedef T type; };
 
-// Launches `kernel` and returns the launch call's own status: the caller's HIP error state
-// (an earlier, unrelated error of the thread) is neither reported nor cleared here.
+// Launches `kernel` with `lds` bytes of dynamic LDS and returns the launch call's own status:
+// the caller's HIP error state (an earlier, unrelated error of the thread) is neither reported
+// nor cleared here.
 template <typename... KArgs>
-int launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t st,
+int launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t st,
            typename same_type<KArgs>::type... args)
 {
     void* ptrs[] = {(void*)&args...};
-    return (int)hipLaunchKernel((const void*)kernel, grid, block, ptrs, 0, st);
+    return (int)hipLaunchKernel((const void*)kernel, grid, block, ptrs, lds, st);
+}
+
+// Launch shape of a kernel family: lanes per workgroup and the most wavefronts a compute unit
+// may hold at a time (0 = whatever fits).
+//
+// Measured on MI355X (same buffers, one process; GB/s of algorithmic bytes): these streaming
+// kernels run fastest in single-wavefront workgroups -- a finished wavefront's slot is refilled
+// at once instead of when the last of a workgroup's 8 wavefronts has finished -- and with fewer
+// wavefronts per compute unit than fit, i.e. with fewer but longer request streams at the memory
+// controllers.  lanes x wavefronts per compute unit (32 = no cap), at 50 M elements (outputs
+// fit the Infinity Cache) / 200 M elements (they do not):
+//   reorder (3.2 GB)  256x32 6335         64x32 6580          64x16 5990           64x8 3860
+//   reduce p = 16     512x32 6190 / 5790  64x32 6295 / 6050   64x10 6365 / 5985    64x4 6150 / 6150
+//   average r = 8     512x32 5935 / 5570  64x32 6325 / 6185   64x12 6370 / 6365    64x8 6140 / 6170
+//   Adam              128x32 6040 / 5715  64x32 5965 / 5830   64x12 6530 / 6305    64x10 6385 / 6510
+//   average + Adam    128x32 5845 / 5560  64x32 5910 / 5865   64x8  6235 / 6155    64x6 6395 / 6370
+// The cap is enforced with otherwise unused dynamic LDS: a workgroup that asks for 1/n of a
+// compute unit's LDS shares the unit with at most n - 1 others.
+struct Shape {
+    int lanes, waves_per_cu;
+};
+constexpr Shape kDefaultShape[kFamilies][2] = {
+    /* reorder */ {{MICS_REORDER_BLOCK, 0}, {MICS_REORDER_BLOCK, 0}},
+    /* reduce  */ {{MICS_RSA_BLOCK, MICS_RSA_WAVES}, {MICS_RSA_BLOCK, MICS_RSA_WAVES_STREAMED}},
+    /* average */ {{MICS_AVG_BLOCK, MICS_AVG_WAVES}, {MICS_AVG_BLOCK, MICS_AVG_WAVES_STREAMED}},
+    /* Adam    */ {{MICS_ADAM_BLOCK, MICS_ADAM_WAVES}, {MICS_ADAM_BLOCK, MICS_ADAM_WAVES_STREAMED}},
+    /* fused   */ {{MICS_FUSED_BLOCK, MICS_FUSED_WAVES}, {MICS_FUSED_BLOCK, MICS_FUSED_WAVES}},
+};
+std::atomic<int> g_lanes[kFamilies], g_waves[kFamilies];       // 0 = built-in choice
+
+// `streams` = buffers a lane reads in this call, `tuned_streams` = the number the built-in cap
+// was measured with: a lane with fewer loads in flight needs proportionally more wavefronts
+// beside it (a lane with more keeps the cap).
+Shape shape_of(int family, bool streamed, int streams = 1, int tuned_streams = 1)
+{
+    Shape sh = kDefaultShape[family][streamed ? 1 : 0];
+    if (sh.waves_per_cu > 0 && streams < tuned_streams)
+        sh.waves_per_cu = (sh.waves_per_cu * tuned_streams + streams - 1) / streams;
+    if (const int l = g_lanes[family].load()) sh.lanes = l;
+    if (const int w = g_waves[family].load()) sh.waves_per_cu = w;
+    if (sh.waves_per_cu >= 32) sh.waves_per_cu = 0;
+    return sh;
+}
+
+// Dynamic LDS that keeps the wavefronts of `sh` on a compute unit at or below its cap, at least
+// `needed` bytes (what the kernel itself uses).  Without an opt-in a workgroup gets at most
+// 64 KiB, so the cap cannot go below 3 workgroups per compute unit.
+size_t lds_for(const Shape& sh, size_t needed = 0)
+{
+    constexpr size_t kLdsPerCu = 160u << 10, kMaxDynamic = 64u << 10;
+    const int waves_per_wg = sh.lanes / 64;
+    if (sh.waves_per_cu <= 0 || sh.waves_per_cu / waves_per_wg >= 32) return needed;
+    size_t wgs = (size_t)sh.waves_per_cu / (size_t)waves_per_wg;
+    if (wgs < 1) wgs = 1;
+    size_t bytes = (kLdsPerCu / wgs) & ~(size_t)255;
+    if (bytes > kMaxDynamic) bytes = kMaxDynamic;
+    return bytes > needed ? bytes : needed;
 }
 
 // Calls f(std::bool_constant<a>, std::bool_constant<b>) for two runtime flags.
@@ -1002,6 +1075,12 @@ void set_blocks_per_cu(int n) { g_blocks_per_cu.store(n); }
 
 void set_stream_threshold_bytes(size_t n) { g_stream_bytes.store(n ? n : kDefaultStreamBytes); }
 
+void set_launch_shape(int family, int lanes, int waves_per_cu)
+{
+    g_lanes[family].store(lanes);
+    g_waves[family].store(waves_per_cu);
+}
+
 const char* hip_error_text(int err) { return hipGetErrorString((hipError_t)err); }
 
 int launch_reorder(void* dst, const PtrTable& src, size_t n_valid_bytes, size_t shard_bytes, int p,
@@ -1011,9 +1090,10 @@ int launch_reorder(void* dst, const PtrTable& src, size_t n_valid_bytes, size_t 
     if (vec16) {
         // spread the block budget over the p chunks
         unsigned total = 0;
-        if (int e = grid_for(shard_bytes / 16 * (size_t)p, kReorderBlock, MICS_REORDER_BPC, &total)) return e;
+        const Shape sh = shape_of(kFamReorder, true);
+        if (int e = grid_for(shard_bytes / 16 * (size_t)p, sh.lanes, MICS_REORDER_BPC, &total)) return e;
         unsigned bx = (total + (unsigned)p - 1) / (unsigned)p;
-        return launch(reorder_vec_kernel, dim3(bx, (unsigned)p), dim3(kReorderBlock), st, (u32x4*)dst, src,
+        return launch(reorder_vec_kernel, dim3(bx, (unsigned)p), dim3(sh.lanes), lds_for(sh), st, (u32x4*)dst, src,
                       shard_bytes / 16, n_valid_bytes, k);
     }
     const Segment one = {n_valid_bytes, shard_bytes, 0, 0};
@@ -1024,14 +1104,16 @@ namespace {
 
 template <int KIND, int VEC, int P, bool ACCUM, bool SA>
 int rsa_launch(float* acc, const PtrTable& g, int p, unsigned lead, size_t count, unsigned blocks,
-               unsigned block, hipStream_t st)
+               const Shape& sh, hipStream_t st)
 {
+    // the streamed-accumulator kernels pass their results through 32 bytes of LDS per lane
+    const size_t lds = lds_for(sh, SA && VEC == 4 && KIND != 2 ? (size_t)sh.lanes * 32 : 0);
     if constexpr (P > 0)
-        return launch(rsa_kernel<KIND, VEC, P, ACCUM, SA, SmallTable<P>>, dim3(blocks + 1), dim3(block), st, acc,
-                      small<P>(g), p, lead, count);
+        return launch(rsa_kernel<KIND, VEC, P, ACCUM, SA, SmallTable<P>>, dim3(blocks + 1), dim3(sh.lanes), lds, st,
+                      acc, small<P>(g), p, lead, count);
     else
-        return launch(rsa_kernel<KIND, VEC, 0, ACCUM, SA, PtrTable>, dim3(blocks + 1), dim3(block), st, acc, g, p,
-                      lead, count);
+        return launch(rsa_kernel<KIND, VEC, 0, ACCUM, SA, PtrTable>, dim3(blocks + 1), dim3(sh.lanes), lds, st, acc,
+                      g, p, lead, count);
 }
 
 template <int KIND>
@@ -1042,29 +1124,36 @@ int rsa_launch_kind(float* acc, const PtrTable& g, int p, unsigned lead, size_t 
     unsigned blocks = 0;
     // small message on a large group: one dword per lane and buffer
     if (p >= MICS_NARROW_MIN_P && count <= (size_t)MICS_NARROW_MAX_ELEMS / (size_t)p) {
+        const Shape narrow = {kNarrowBlock, 0};
         const size_t nlanes = (lead + count + PD - 1) / PD;
         if (int e = grid_for(nlanes, kNarrowBlock, MICS_RSA_BPC, &blocks)) return e;
-        return accumulate ? rsa_launch<KIND, 1, 0, true, false>(acc, g, p, lead, count, blocks, kNarrowBlock, st)
-                          : rsa_launch<KIND, 1, 0, false, false>(acc, g, p, lead, count, blocks, kNarrowBlock, st);
+        return accumulate ? rsa_launch<KIND, 1, 0, true, false>(acc, g, p, lead, count, blocks, narrow, st)
+                          : rsa_launch<KIND, 1, 0, false, false>(acc, g, p, lead, count, blocks, narrow, st);
     }
     const size_t nlanes = (lead + count + 4 * PD - 1) / (4 * PD);
-    // Full-size workgroups once they give every compute unit one; single wavefronts below that,
-    // so that a call of a few MB is spread over the chip instead of over a handful of units
+    const bool streamed = stream_acc(count);
+    Shape sh = shape_of(kFamReduce, streamed, p + 2, 18);
+    // Single-wavefront workgroups are the fastest when every access is 16-byte aligned; with the
+    // accumulator or the gradients off that alignment full-size workgroups are (6070 against
+    // 5740 GB/s at 50 M elements), unless the call is too small to give every compute unit one
     // (a unit moves about 100 GB/s on its own).
     int cus = 0;
     if (int e = compute_units(&cus)) return e;
-    const unsigned block = nlanes >= (size_t)kRsaBlock * (size_t)cus ? kRsaBlock : MICS_RSA_SMALL_BLOCK;
-    if (int e = grid_for(nlanes, (int)block, MICS_RSA_BPC, &blocks)) return e;
-    return dispatch2(accumulate, stream_acc(count), [&](auto A, auto SA) {
+    bool aligned16 = lead == 0 && ((uintptr_t)acc & 15) == 0;
+    for (int q = 0; q < p && aligned16; ++q) aligned16 = ((uintptr_t)g.ptr[q] & 15) == 0;
+    if (!aligned16 && g_lanes[kFamReduce].load() == 0 && nlanes >= (size_t)MICS_RSA_UNALIGNED_BLOCK * (size_t)cus)
+        sh = Shape{MICS_RSA_UNALIGNED_BLOCK, 0};
+    if (int e = grid_for(nlanes, sh.lanes, MICS_RSA_BPC, &blocks)) return e;
+    return dispatch2(accumulate, streamed, [&](auto A, auto SA) {
         if constexpr (KIND == 0) {
             return dispatch_group(p, [&](auto P) {
-                return rsa_launch<KIND, 4, P.value, A.value, SA.value>(acc, g, p, lead, count, blocks, block, st);
+                return rsa_launch<KIND, 4, P.value, A.value, SA.value>(acc, g, p, lead, count, blocks, sh, st);
             });
         } else {
             switch (p) {
-                case 8: return rsa_launch<KIND, 4, 8, A.value, SA.value>(acc, g, p, lead, count, blocks, block, st);
-                case 16: return rsa_launch<KIND, 4, 16, A.value, SA.value>(acc, g, p, lead, count, blocks, block, st);
-                default: return rsa_launch<KIND, 4, 0, A.value, SA.value>(acc, g, p, lead, count, blocks, block, st);
+                case 8: return rsa_launch<KIND, 4, 8, A.value, SA.value>(acc, g, p, lead, count, blocks, sh, st);
+                case 16: return rsa_launch<KIND, 4, 16, A.value, SA.value>(acc, g, p, lead, count, blocks, sh, st);
+                default: return rsa_launch<KIND, 4, 0, A.value, SA.value>(acc, g, p, lead, count, blocks, sh, st);
             }
         }
     });
@@ -1107,14 +1196,18 @@ int launch_replica_average(float* out, const PtrTable& a, size_t count, int r, f
 {
     hipStream_t st = (hipStream_t)stream;
     unsigned blocks = 0;
-    if (int e = grid_for((count + 3) / 4, kAvgBlock, MICS_AVG_BPC, &blocks)) return e;
-    return dispatch2(stream_acc(count), false, [&](auto SO, auto) {
+    const bool streamed = stream_acc(count);
+    const Shape sh = shape_of(kFamAverage, streamed, r + 1, 9);
+    const size_t lds = lds_for(sh);
+    if (int e = grid_for((count + 3) / 4, sh.lanes, MICS_AVG_BPC, &blocks)) return e;
+    const dim3 gr(blocks), bl(sh.lanes);
+    return dispatch2(streamed, false, [&](auto SO, auto) {
         switch (r) {
-            case 1: return launch(avg_kernel<1, SO.value, SmallTable<1>>, dim3(blocks), dim3(kAvgBlock), st, out, small<1>(a), r, scale, count);
-            case 2: return launch(avg_kernel<2, SO.value, SmallTable<2>>, dim3(blocks), dim3(kAvgBlock), st, out, small<2>(a), r, scale, count);
-            case 4: return launch(avg_kernel<4, SO.value, SmallTable<4>>, dim3(blocks), dim3(kAvgBlock), st, out, small<4>(a), r, scale, count);
-            case 8: return launch(avg_kernel<8, SO.value, SmallTable<8>>, dim3(blocks), dim3(kAvgBlock), st, out, small<8>(a), r, scale, count);
-            default: return launch(avg_kernel<0, SO.value, PtrTable>, dim3(blocks), dim3(kAvgBlock), st, out, a, r, scale, count);
+            case 1: return launch(avg_kernel<1, SO.value, SmallTable<1>>, gr, bl, lds, st, out, small<1>(a), r, scale, count);
+            case 2: return launch(avg_kernel<2, SO.value, SmallTable<2>>, gr, bl, lds, st, out, small<2>(a), r, scale, count);
+            case 4: return launch(avg_kernel<4, SO.value, SmallTable<4>>, gr, bl, lds, st, out, small<4>(a), r, scale, count);
+            case 8: return launch(avg_kernel<8, SO.value, SmallTable<8>>, gr, bl, lds, st, out, small<8>(a), r, scale, count);
+            default: return launch(avg_kernel<0, SO.value, PtrTable>, gr, bl, lds, st, out, a, r, scale, count);
         }
     });
 }
@@ -1124,11 +1217,12 @@ int launch_adam(float* master, float* exp_avg, float* exp_avg_sq, uint16_t* para
 {
     hipStream_t st = (hipStream_t)stream;
     unsigned blocks = 0;
-    if (int e = grid_for((count + 3) / 4, kAdamBlock, MICS_ADAM_BPC, &blocks)) return e;
+    const Shape sh = shape_of(kFamAdam, stream_acc(count));
+    if (int e = grid_for((count + 3) / 4, sh.lanes, MICS_ADAM_BPC, &blocks)) return e;
     if (param_bf16)
-        return launch(adam_kernel<true>, dim3(blocks), dim3(kAdamBlock), st, master, exp_avg, exp_avg_sq,
+        return launch(adam_kernel<true>, dim3(blocks), dim3(sh.lanes), lds_for(sh), st, master, exp_avg, exp_avg_sq,
                       param_bf16, grad, count, hp);
-    return launch(adam_kernel<false>, dim3(blocks), dim3(kAdamBlock), st, master, exp_avg, exp_avg_sq,
+    return launch(adam_kernel<false>, dim3(blocks), dim3(sh.lanes), lds_for(sh), st, master, exp_avg, exp_avg_sq,
                   param_bf16, grad, count, hp);
 }
 
@@ -1155,7 +1249,7 @@ int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs
             }
             for (int t = nt; t <= kMaxSeg; ++t) tab.tile_begin[t] = 0xFFFFFFFFu;
             if (tiles == 0) continue;
-            if (int e = launch(reorder_seg_kernel, dim3((unsigned)tiles, (unsigned)p), dim3(kSegBlock), st,
+            if (int e = launch(reorder_seg_kernel, dim3((unsigned)tiles, (unsigned)p), dim3(kSegBlock), 0, st,
                                (u32x4*)dst, src, tab, k))
                 return e;
         } else {
@@ -1169,7 +1263,7 @@ int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs
                 tiles = sg.numel ? (one.seg.shard_bytes + 15 + kTileBytes - 1) / kTileBytes : 0;
                 if (tiles > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
                 if (tiles == 0) continue;
-                if (int e = launch(reorder_lds_kernel<LdsOneTensor>, dim3((unsigned)tiles, (unsigned)p), dim3(kBlock), st,
+                if (int e = launch(reorder_lds_kernel<LdsOneTensor>, dim3((unsigned)tiles, (unsigned)p), dim3(kBlock), 0, st,
                                    (unsigned char*)dst, src, one, k))
                     return e;
                 continue;
@@ -1189,7 +1283,7 @@ int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs
             }
             for (int t = nt; t <= kMaxSeg; ++t) tab.tile_begin[t] = 0xFFFFFFFFu;
             if (tiles == 0) continue;
-            if (int e = launch(reorder_lds_kernel<LdsSegTable>, dim3((unsigned)tiles, (unsigned)p), dim3(kBlock), st,
+            if (int e = launch(reorder_lds_kernel<LdsSegTable>, dim3((unsigned)tiles, (unsigned)p), dim3(kBlock), 0, st,
                                (unsigned char*)dst, src, tab, k))
                 return e;
         }
@@ -1201,16 +1295,21 @@ int launch_reduce_coalesced(float* acc, const PtrTable& grads, const Segment* se
                             bool accumulate, void* stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    constexpr size_t kTileElems = (size_t)kRsaBlock * 8;
     PtrTable g = grads;
     const size_t base_lead = align_gradient_pointers(g, p, 2);
     for (int first = 0; first < n; first += kMaxSeg) {
         ReduceSegTable tab;
         tab.n = n - first < kMaxSeg ? n - first : kMaxSeg;
-        size_t tiles = 0, elements = 0;
+        size_t elements = 0;
+        for (int t = 0; t < tab.n; ++t) elements += segs[first + t].numel;
+        const bool streamed = stream_acc(elements);
+        // tensors of a layer start anywhere: full-size workgroups (see rsa_launch_kind)
+        Shape sh = shape_of(kFamReduce, streamed);
+        if (g_lanes[kFamReduce].load() == 0) sh = Shape{MICS_RSA_UNALIGNED_BLOCK, 0};
+        const size_t tile_elems = (size_t)sh.lanes * 8;
+        size_t tiles = 0;
         for (int t = 0; t < tab.n; ++t) {
             const Segment& sg = segs[first + t];
-            elements += sg.numel;
             // position of the segment's first element in the rounded-down buffers; its virtual
             // element 0 is the even position at or below it
             const size_t src = sg.src_offset + base_lead;
@@ -1221,20 +1320,21 @@ int launch_reduce_coalesced(float* acc, const PtrTable& grads, const Segment* se
             tab.seg[t].end = lead + sg.numel;
             tab.seg[t].src0 = src - lead;
             tab.seg[t].dst = sg.dst_offset;
-            if (sg.numel) tiles += (lead + sg.numel + kTileElems - 1) / kTileElems;
+            if (sg.numel) tiles += (lead + sg.numel + tile_elems - 1) / tile_elems;
             else tab.seg[t].end = 0;
             if (tiles > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
         }
         for (int t = tab.n; t <= kMaxSeg; ++t) tab.tile_begin[t] = 0xFFFFFFFFu;
         if (tiles == 0) continue;
-        const int err = dispatch2(accumulate, stream_acc(elements), [&](auto A, auto SA) {
+        const int err = dispatch2(accumulate, streamed, [&](auto A, auto SA) {
+            const size_t lds = lds_for(sh, SA.value ? (size_t)sh.lanes * 32 : 0);
             return dispatch_group(p, [&](auto P) {
                 if constexpr (P.value > 0)
                     return launch(rsa_seg_kernel<P.value, A.value, SA.value, SmallTable<P.value>>,
-                                  dim3((unsigned)tiles), dim3(kRsaBlock), st, acc, small<P.value>(g), p, tab);
+                                  dim3((unsigned)tiles), dim3(sh.lanes), lds, st, acc, small<P.value>(g), p, tab);
                 else
                     return launch(rsa_seg_kernel<0, A.value, SA.value, PtrTable>, dim3((unsigned)tiles),
-                                  dim3(kRsaBlock), st, acc, g, p, tab);
+                                  dim3(sh.lanes), lds, st, acc, g, p, tab);
             });
         });
         if (err) return err;
@@ -1248,15 +1348,17 @@ int launch_avg_adam(float* master, float* exp_avg, float* exp_avg_sq, uint16_t* 
 {
     hipStream_t st = (hipStream_t)stream;
     unsigned blocks = 0;
-    if (int e = grid_for((count + 3) / 4, kFusedBlock, MICS_ADAM_BPC, &blocks)) return e;
+    const Shape sh = shape_of(kFamFused, stream_acc(count), r + 3, 11);
+    const size_t lds = lds_for(sh);
+    if (int e = grid_for((count + 3) / 4, sh.lanes, MICS_ADAM_BPC, &blocks)) return e;
     return dispatch2(param_bf16 != nullptr, false, [&](auto BF, auto) {
-        const dim3 gr(blocks), bl(kFusedBlock);
+        const dim3 gr(blocks), bl(sh.lanes);
         switch (r) {
-            case 1: return launch(avg_adam_kernel<1, BF.value, SmallTable<1>>, gr, bl, st, master, exp_avg, exp_avg_sq, param_bf16, small<1>(copies), r, scale, count, hp);
-            case 2: return launch(avg_adam_kernel<2, BF.value, SmallTable<2>>, gr, bl, st, master, exp_avg, exp_avg_sq, param_bf16, small<2>(copies), r, scale, count, hp);
-            case 4: return launch(avg_adam_kernel<4, BF.value, SmallTable<4>>, gr, bl, st, master, exp_avg, exp_avg_sq, param_bf16, small<4>(copies), r, scale, count, hp);
-            case 8: return launch(avg_adam_kernel<8, BF.value, SmallTable<8>>, gr, bl, st, master, exp_avg, exp_avg_sq, param_bf16, small<8>(copies), r, scale, count, hp);
-            default: return launch(avg_adam_kernel<0, BF.value, PtrTable>, gr, bl, st, master, exp_avg, exp_avg_sq, param_bf16, copies, r, scale, count, hp);
+            case 1: return launch(avg_adam_kernel<1, BF.value, SmallTable<1>>, gr, bl, lds, st, master, exp_avg, exp_avg_sq, param_bf16, small<1>(copies), r, scale, count, hp);
+            case 2: return launch(avg_adam_kernel<2, BF.value, SmallTable<2>>, gr, bl, lds, st, master, exp_avg, exp_avg_sq, param_bf16, small<2>(copies), r, scale, count, hp);
+            case 4: return launch(avg_adam_kernel<4, BF.value, SmallTable<4>>, gr, bl, lds, st, master, exp_avg, exp_avg_sq, param_bf16, small<4>(copies), r, scale, count, hp);
+            case 8: return launch(avg_adam_kernel<8, BF.value, SmallTable<8>>, gr, bl, lds, st, master, exp_avg, exp_avg_sq, param_bf16, small<8>(copies), r, scale, count, hp);
+            default: return launch(avg_adam_kernel<0, BF.value, PtrTable>, gr, bl, lds, st, master, exp_avg, exp_avg_sq, param_bf16, copies, r, scale, count, hp);
         }
     });
 }

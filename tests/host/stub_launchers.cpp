@@ -23,5 +23,6 @@ int launch_reduce_coalesced(float*, const PtrTable&, const Segment*, int n, int,
 }
 void set_blocks_per_cu(int) {}
 void set_stream_threshold_bytes(size_t) {}
+void set_launch_shape(int, int, int) {}
 const char* hip_error_text(int) { return "stub"; }
 }  // namespace mics
