@@ -69,6 +69,10 @@ def parse_args():
                     help="the Adam step writes its bf16 shard straight into the stage-1 buffer of the next "
                          "parameter gather (at T_l + j*S) instead of a buffer of its own")
     ap.add_argument("--blocks-per-cu", type=int, default=0)
+    ap.add_argument("--launch-shape", action="append", default=[], metavar="FAMILY:LANES:WAVES",
+                    help="launch shape of a kernel family (reorder, reduce, average, adam, fused): lanes per "
+                         "workgroup and wavefronts per compute unit, 0 = built-in choice (mics_set_launch_shape); "
+                         "may be given several times")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-group-view", action="store_true",
                     help="skip the whole-group view that follows the rank-view steps")
@@ -380,7 +384,7 @@ class Workload:
                             f"({count} elements per reduce/average/Adam call)"
                             + (", coalesced: 16 separately sharded tensors" if a.coalesced else ""),
                 "view": self.view, "coalesced": bool(a.coalesced), "fused_average_adam": bool(a.fused),
-                "adam_writes_stage1_buffer": bool(a.stage1_out),
+                "adam_writes_stage1_buffer": bool(a.stage1_out), "launch_shape_overrides": list(a.launch_shape),
                 "gathers_per_microstep": a.gathers_per_microstep, "N": N, "S": self.S, "p": p, "k": k, "r": r, "s": s,
                 "algorithmic_bytes_per_step": b_step,
                 "accumulator_bytes": 4 * count,
@@ -433,6 +437,11 @@ def main():
     torch.cuda.set_device(torch.device("cuda:0"))
     if args.blocks_per_cu:
         mics.mics_set_blocks_per_cu(args.blocks_per_cu)
+    families = {"reorder": mics.MICS_KERNELS_REORDER, "reduce": mics.MICS_KERNELS_REDUCE,
+                "average": mics.MICS_KERNELS_AVERAGE, "adam": mics.MICS_KERNELS_ADAM, "fused": mics.MICS_KERNELS_FUSED}
+    for spec in args.launch_shape:
+        fam, lanes, waves = spec.split(":")
+        mics.mics_set_launch_shape(families[fam], int(lanes), int(waves))
 
     wl = Workload(args, args.view, mics, synth, torch, np)
     result = wl.run(args.steps, args.warmup)

@@ -97,7 +97,7 @@ typedef f32x2 f32x2_a4 __attribute__((aligned(4)));
 #define MICS_AVG_WAVES 12
 #endif
 #ifndef MICS_AVG_WAVES_STREAMED
-#define MICS_AVG_WAVES_STREAMED 12
+#define MICS_AVG_WAVES_STREAMED 10
 #endif
 #ifndef MICS_AVG_BPC
 #define MICS_AVG_BPC 4096
@@ -112,13 +112,16 @@ typedef f32x2 f32x2_a4 __attribute__((aligned(4)));
 #define MICS_ADAM_WAVES 12
 #endif
 #ifndef MICS_ADAM_WAVES_STREAMED
-#define MICS_ADAM_WAVES_STREAMED 10
+#define MICS_ADAM_WAVES_STREAMED 9
 #endif
 #ifndef MICS_FUSED_BLOCK
 #define MICS_FUSED_BLOCK 64
 #endif
 #ifndef MICS_FUSED_WAVES
 #define MICS_FUSED_WAVES 6
+#endif
+#ifndef MICS_FUSED_WAVES_STREAMED
+#define MICS_FUSED_WAVES_STREAMED 5
 #endif
 #ifndef MICS_FUSED_COPIES_FIRST
 #define MICS_FUSED_COPIES_FIRST 1
@@ -266,19 +269,18 @@ __global__ __launch_bounds__(kMaxBlock) void reorder_vec_kernel(
 
 // Coalesced form (many separately sharded tensors in one launch, all 16-byte aligned):
 // blockIdx.y = chunk g, blockIdx.x = tile x - tile_begin[t] of tensor t's chunk.  A tile is
-// MICS_SEG_U runs of kSegBlock vectors.  Measured on the h = 8192 layer (GB/s): 256 lanes x 1:
-// 5200, x 2: 6100, x 4: 5900; 512 x 1: 4600; 1024 x 1: 3600 -- the table look-up in every
-// wavefront's prologue has to be paid for by two vectors per lane, more spreads the window.
-// A small chunk (a bias of h/p elements) costs one workgroup.
+// MICS_SEG_U runs of blockDim.x vectors: the table look-up in every wavefront's prologue has to
+// be paid for by two vectors per lane (one: -15 %), more spreads the window (four: -3 %).
+// Measured on the h = 8192 layer with two vectors per lane (GB/s): 64 lanes 6375, 128: 6340,
+// 256: 6200, 512: 5950.  A small chunk (a bias of h/p elements) costs one workgroup.
 #ifndef MICS_SEG_BLOCK
-#define MICS_SEG_BLOCK 256
+#define MICS_SEG_BLOCK 64
 #endif
+constexpr int kSegLanes = MICS_SEG_BLOCK;
 #ifndef MICS_SEG_U
 #define MICS_SEG_U 2
 #endif
 constexpr int kMaxSeg = kMaxSegPerLaunch;
-constexpr int kSegBlock = MICS_SEG_BLOCK;
-constexpr int kSegTileVecs = kSegBlock * MICS_SEG_U;
 
 // Index of the segment whose tile range holds workgroup x: tile_begin is ascending, unused
 // entries hold 0xFFFFFFFF.  Counting instead of walking keeps the table reads independent of
@@ -299,7 +301,7 @@ struct ReorderSegTable {
     ReorderSeg seg[kMaxSeg];
 };
 
-__global__ __launch_bounds__(kSegBlock) void reorder_seg_kernel(
+__global__ __launch_bounds__(kMaxBlock) void reorder_seg_kernel(
     u32x4* __restrict__ dst, PtrTable src, ReorderSegTable tab, int k)
 {
     const unsigned x = blockIdx.x;
@@ -314,21 +316,22 @@ __global__ __launch_bounds__(kSegBlock) void reorder_seg_kernel(
     const size_t j = g / (size_t)k, l = g % (size_t)k;
     const u32x4* __restrict__ s = (const u32x4*)src.ptr[l] + tab.seg[t].src_vec + j * shard_vecs;
     u32x4* __restrict__ d = dst + tab.seg[t].dst_vec + g * shard_vecs;
-    const size_t tile0 = (size_t)(x - tab.tile_begin[t]) * kSegTileVecs;
+    const size_t tile_vecs = (size_t)blockDim.x * MICS_SEG_U;
+    const size_t tile0 = (size_t)(x - tab.tile_begin[t]) * tile_vecs;
     u32x4 v[MICS_SEG_U];
     #pragma unroll
     for (int u = 0; u < MICS_SEG_U; ++u) {
-        const size_t i = tile0 + (size_t)u * kSegBlock + threadIdx.x;
+        const size_t i = tile0 + (size_t)u * blockDim.x + threadIdx.x;
         if (i < nfull) v[u] = MICS_LD(kReorderNtl, s + i);
     }
     #pragma unroll
     for (int u = 0; u < MICS_SEG_U; ++u) {
-        const size_t i = tile0 + (size_t)u * kSegBlock + threadIdx.x;
+        const size_t i = tile0 + (size_t)u * blockDim.x + threadIdx.x;
         if (i < nfull) MICS_ST(kReorderNts, d + i, v[u]);
     }
     // ragged end of the tensor: the tile that holds vector index nfull moves the last bytes
     const size_t tail_halves = (valid - nfull * 16) / 2;
-    if (tail_halves && nfull / kSegTileVecs == x - tab.tile_begin[t] && threadIdx.x < tail_halves) {
+    if (tail_halves && nfull / tile_vecs == x - tab.tile_begin[t] && threadIdx.x < tail_halves) {
         const uint16_t* sh = (const uint16_t*)(s + nfull);
         uint16_t* dh = (uint16_t*)(d + nfull);
         dh[threadIdx.x] = sh[threadIdx.x];
@@ -1005,16 +1008,17 @@ constexpr Shape kDefaultShape[kFamilies][2] = {
     /* reduce  */ {{MICS_RSA_BLOCK, MICS_RSA_WAVES}, {MICS_RSA_BLOCK, MICS_RSA_WAVES_STREAMED}},
     /* average */ {{MICS_AVG_BLOCK, MICS_AVG_WAVES}, {MICS_AVG_BLOCK, MICS_AVG_WAVES_STREAMED}},
     /* Adam    */ {{MICS_ADAM_BLOCK, MICS_ADAM_WAVES}, {MICS_ADAM_BLOCK, MICS_ADAM_WAVES_STREAMED}},
-    /* fused   */ {{MICS_FUSED_BLOCK, MICS_FUSED_WAVES}, {MICS_FUSED_BLOCK, MICS_FUSED_WAVES}},
+    /* fused   */ {{MICS_FUSED_BLOCK, MICS_FUSED_WAVES}, {MICS_FUSED_BLOCK, MICS_FUSED_WAVES_STREAMED}},
 };
 std::atomic<int> g_lanes[kFamilies], g_waves[kFamilies];       // 0 = built-in choice
 
 // `streams` = buffers a lane reads in this call, `tuned_streams` = the number the built-in cap
 // was measured with: a lane with fewer loads in flight needs proportionally more wavefronts
 // beside it (a lane with more keeps the cap).
-Shape shape_of(int family, bool streamed, int streams = 1, int tuned_streams = 1)
+Shape shape_of(int family, bool streamed, int streams = 1, int tuned_streams = 1, int default_lanes = 0)
 {
     Shape sh = kDefaultShape[family][streamed ? 1 : 0];
+    if (default_lanes) sh.lanes = default_lanes;
     if (sh.waves_per_cu > 0 && streams < tuned_streams)
         sh.waves_per_cu = (sh.waves_per_cu * tuned_streams + streams - 1) / streams;
     if (const int l = g_lanes[family].load()) sh.lanes = l;
@@ -1143,6 +1147,9 @@ int rsa_launch_kind(float* acc, const PtrTable& g, int p, unsigned lead, size_t 
     for (int q = 0; q < p && aligned16; ++q) aligned16 = ((uintptr_t)g.ptr[q] & 15) == 0;
     if (!aligned16 && g_lanes[kFamReduce].load() == 0 && nlanes >= (size_t)MICS_RSA_UNALIGNED_BLOCK * (size_t)cus)
         sh = Shape{MICS_RSA_UNALIGNED_BLOCK, 0};
+    // binary16 gradients cost a conversion per element: the arithmetic then needs every wavefront
+    // that fits (p = 16, 50 M elements: 6430 GB/s uncapped, 4450 with 10 wavefronts per unit)
+    if (KIND == 1 && g_waves[kFamReduce].load() == 0) sh.waves_per_cu = 0;
     if (int e = grid_for(nlanes, sh.lanes, MICS_RSA_BPC, &blocks)) return e;
     return dispatch2(accumulate, streamed, [&](auto A, auto SA) {
         if constexpr (KIND == 0) {
@@ -1235,6 +1242,8 @@ int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs
         const int nt = n - first < kMaxSeg ? n - first : kMaxSeg;
         size_t tiles = 0;
         if (vec16) {
+            const Shape sh = shape_of(kFamReorder, true, 1, 1, kSegLanes);
+            const size_t tile_vecs = (size_t)sh.lanes * MICS_SEG_U;
             ReorderSegTable tab;
             tab.n = nt;
             for (int t = 0; t < nt; ++t) {
@@ -1244,15 +1253,18 @@ int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs
                 tab.seg[t].valid_bytes = sg.numel * eb;
                 tab.seg[t].src_vec = sg.src_offset * eb / 16;
                 tab.seg[t].dst_vec = sg.dst_offset * eb / 16;
-                tiles += (tab.seg[t].shard_vecs + kSegTileVecs - 1) / kSegTileVecs;
+                tiles += (tab.seg[t].shard_vecs + tile_vecs - 1) / tile_vecs;
                 if (tiles > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
             }
             for (int t = nt; t <= kMaxSeg; ++t) tab.tile_begin[t] = 0xFFFFFFFFu;
             if (tiles == 0) continue;
-            if (int e = launch(reorder_seg_kernel, dim3((unsigned)tiles, (unsigned)p), dim3(kSegBlock), 0, st,
+            if (int e = launch(reorder_seg_kernel, dim3((unsigned)tiles, (unsigned)p), dim3(sh.lanes), lds_for(sh), st,
                                (u32x4*)dst, src, tab, k))
                 return e;
         } else {
+            // fixed 256-lane tiles; the family's cap on wavefronts per compute unit applies
+            const Shape lds_shape = {kBlock, shape_of(kFamReorder, true, 1, 1, kBlock).waves_per_cu};
+            const size_t lds_cap = lds_for(lds_shape);
             if (nt == 1) {
                 const Segment& sg = segs[first];
                 LdsOneTensor one;
@@ -1263,7 +1275,7 @@ int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs
                 tiles = sg.numel ? (one.seg.shard_bytes + 15 + kTileBytes - 1) / kTileBytes : 0;
                 if (tiles > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
                 if (tiles == 0) continue;
-                if (int e = launch(reorder_lds_kernel<LdsOneTensor>, dim3((unsigned)tiles, (unsigned)p), dim3(kBlock), 0, st,
+                if (int e = launch(reorder_lds_kernel<LdsOneTensor>, dim3((unsigned)tiles, (unsigned)p), dim3(kBlock), lds_cap, st,
                                    (unsigned char*)dst, src, one, k))
                     return e;
                 continue;
@@ -1283,7 +1295,7 @@ int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs
             }
             for (int t = nt; t <= kMaxSeg; ++t) tab.tile_begin[t] = 0xFFFFFFFFu;
             if (tiles == 0) continue;
-            if (int e = launch(reorder_lds_kernel<LdsSegTable>, dim3((unsigned)tiles, (unsigned)p), dim3(kBlock), 0, st,
+            if (int e = launch(reorder_lds_kernel<LdsSegTable>, dim3((unsigned)tiles, (unsigned)p), dim3(kBlock), lds_cap, st,
                                (unsigned char*)dst, src, tab, k))
                 return e;
         }
@@ -1303,9 +1315,14 @@ int launch_reduce_coalesced(float* acc, const PtrTable& grads, const Segment* se
         size_t elements = 0;
         for (int t = 0; t < tab.n; ++t) elements += segs[first + t].numel;
         const bool streamed = stream_acc(elements);
-        // tensors of a layer start anywhere: full-size workgroups (see rsa_launch_kind)
-        Shape sh = shape_of(kFamReduce, streamed);
-        if (g_lanes[kFamReduce].load() == 0) sh = Shape{MICS_RSA_UNALIGNED_BLOCK, 0};
+        // as in rsa_launch_kind: single-wavefront workgroups if every access is 16-byte aligned
+        // (h = 8192 layer: 6460 against 6220 GB/s), full-size ones otherwise
+        Shape sh = shape_of(kFamReduce, streamed, p + 2, 18);
+        bool aligned16 = base_lead == 0 && ((uintptr_t)acc & 15) == 0;
+        for (int q = 0; q < p && aligned16; ++q) aligned16 = ((uintptr_t)g.ptr[q] & 15) == 0;
+        for (int t = 0; t < tab.n && aligned16; ++t)
+            aligned16 = segs[first + t].src_offset % 8 == 0 && segs[first + t].dst_offset % 4 == 0;
+        if (!aligned16 && g_lanes[kFamReduce].load() == 0) sh = Shape{MICS_RSA_UNALIGNED_BLOCK, 0};
         const size_t tile_elems = (size_t)sh.lanes * 8;
         size_t tiles = 0;
         for (int t = 0; t < tab.n; ++t) {

@@ -124,6 +124,8 @@ int main()
     CHECK(mics_adam_shard(nullptr, nullptr, nullptr, nullptr, nullptr, 0, 1e-4f, 0.9f, 0.999f, 1e-8f, 0.0f, 1, nullptr) == MICS_OK);
     CHECK(mics::g_launches == before);
     CHECK(mics_set_stream_threshold_bytes(1) == MICS_OK && mics_set_stream_threshold_bytes(0) == MICS_OK);
+    CHECK(mics_set_launch_shape(MICS_KERNELS_REDUCE, 128, 8) == MICS_OK && mics_set_launch_shape(MICS_KERNELS_REDUCE, 0, 0) == MICS_OK);
+    CHECK(mics_set_launch_shape(7, 64, 8) == MICS_ERR_INVALID_ARG && mics_set_launch_shape(0, 100, 8) == MICS_ERR_INVALID_ARG);
     CHECK(mics_shard_elems(805412864, 16, 8) == 50338304);
     std::puts("host checks ok");
     return 0;

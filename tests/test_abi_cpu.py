@@ -145,6 +145,14 @@ def test_launch_knob_range():
         mics.mics_set_blocks_per_cu(4097)
     with pytest.raises(mics.MicsError):
         mics.mics_set_blocks_per_cu(-1)
+    mics.mics_set_stream_threshold_bytes(1)
+    mics.mics_set_stream_threshold_bytes(0)
+    for fam in range(5):
+        mics.mics_set_launch_shape(fam, 128, 8)
+        mics.mics_set_launch_shape(fam, 0, 0)
+    for bad in [(5, 64, 8), (-1, 64, 8), (1, 96, 8), (1, 1024, 8), (1, 64, 33), (1, 64, -1)]:
+        with pytest.raises(mics.MicsError):
+            mics.mics_set_launch_shape(*bad)
 
 
 def test_header_is_valid_c99_and_cxx(tmp_path):

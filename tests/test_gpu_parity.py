@@ -811,3 +811,72 @@ def test_streaming_kernels_give_the_same_results(orc, gen):
             assert out.guards_intact()
     finally:
         mics.mics_set_stream_threshold_bytes(0)
+
+
+# ---- launch shapes ------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("lanes,waves", [(64, 3), (128, 8), (256, 32), (512, 4), (512, 32)])
+def test_launch_shapes_give_the_same_results(orc, gen, lanes, waves):
+    """Workgroup size and the cap on wavefronts per compute unit are measurement knobs: every
+    shape must give the results of the built-in one (flat and coalesced, cacheable and streamed
+    accumulators, all kernel families)."""
+    p, k, r, S = 16, 8, 8, 70000 + 8
+    n = p * S - 5
+    tab = gen.normal_table(1e-3, "bf16")
+    families = (mics.MICS_KERNELS_REORDER, mics.MICS_KERNELS_REDUCE, mics.MICS_KERNELS_AVERAGE,
+                mics.MICS_KERNELS_ADAM, mics.MICS_KERNELS_FUSED)
+    try:
+        for fam in families:
+            mics.mics_set_launch_shape(fam, lanes, waves)
+        shards = [tagged(gen, 5000 + g, S, np.uint16) for g in range(p)]
+        T = [orc.stage1_gather(shards, k, l) for l in range(k)]
+        dst = Guarded(p * S, np.uint16)
+        mics.mics_hier_gather_reorder(dst.t, [upload(t) for t in T], n, S, p, k, 2)
+        torch.cuda.synchronize()
+        assert np.array_equal(dst.numpy()[:n], orc.concat_shards(shards, n)) and dst.guards_intact()
+        for threshold in (0, 1):                       # cacheable, then streamed accumulators
+            mics.mics_set_stream_threshold_bytes(threshold)
+            for off in (0, 3):
+                acc = Guarded(S, np.float32)
+                ref = np.empty(S, np.float32)
+                for t in range(2):
+                    host = [gen.fill_host(gen.stream_key(1800, gen.ROLE_GRAD, 0, t, q), 0, S + 8, tab) for q in range(p)]
+                    mics.mics_reduce_scatter_accum(acc.t, [upload(h) for h in host], off, S, t > 0)
+                    orc.reduce_scatter_accum(ref, host, off, t > 0)
+                torch.cuda.synchronize()
+                assert np.array_equal(acc.numpy().view(np.uint32), ref.view(np.uint32)) and acc.guards_intact()
+            lay = gen.coalesced_layout([512 * 16, 16 * 9000, 16 * 8, 1001], p, k, align=8)
+            segs = lay.reduce_segments(3)
+            host = [gen.fill_host(gen.stream_key(1801, gen.ROLE_GRAD, 0, 0, q), 0, lay.grad_off[-1], tab) for q in range(p)]
+            acc = Guarded(lay.shard_off[-1], np.float32)
+            ref = np.full(lay.shard_off[-1], np.nan, np.float32)
+            mics.mics_reduce_scatter_accum_coalesced(acc.t, [upload(h) for h in host], segs, False)
+            orc.reduce_scatter_accum_coalesced(ref, host, segs, False)
+            torch.cuda.synchronize()
+            assert np.array_equal(acc.numpy().view(np.uint32), ref.view(np.uint32)) and acc.guards_intact()
+            atab = gen.normal_table(1e-2, "f32")
+            copies = [gen.fill_host(gen.stream_key(1802, gen.ROLE_ACC, c), 0, S + 3, atab) for c in range(r)]
+            copies_d = [upload(c) for c in copies]
+            avg = Guarded(S + 3, np.float32)
+            mics.mics_replica_average(avg.t, copies_d, S + 3, 0.25)
+            avg_ref = orc.replica_average(copies, 0.25)
+            torch.cuda.synchronize()
+            assert np.array_equal(avg.numpy().view(np.uint32), avg_ref.view(np.uint32)) and avg.guards_intact()
+        mics.mics_set_stream_threshold_bytes(0)
+        w0 = gen.fill_host(gen.stream_key(1803, gen.ROLE_MASTER), 0, S + 3, gen.normal_table(0.02, "f32"))
+        wr, mr, vr = w0.copy(), np.zeros(S + 3, np.float32), np.zeros(S + 3, np.float32)
+        pbr = orc.adam_shard(wr, mr, vr, avg_ref, step=2, f32=True, **HP)
+        for fused in (False, True):
+            w, m, v = upload(w0.copy()), upload(np.zeros(S + 3, np.float32)), upload(np.zeros(S + 3, np.float32))
+            pb = Guarded(S + 3, np.uint16)
+            if fused:
+                mics.mics_replica_average_adam_shard(w, m, v, pb.t, copies_d, S + 3, 0.25, step=2, **HP)
+            else:
+                mics.mics_adam_shard(w, m, v, pb.t, avg.t, S + 3, step=2, **HP)
+            torch.cuda.synchronize()
+            assert np.array_equal(w.cpu().numpy().view(np.uint32), wr.view(np.uint32))
+            assert np.array_equal(pb.numpy(), pbr) and pb.guards_intact()
+    finally:
+        mics.mics_set_stream_threshold_bytes(0)
+        for fam in families:
+            mics.mics_set_launch_shape(fam, 0, 0)
