@@ -1012,15 +1012,26 @@ constexpr Shape kDefaultShape[kFamilies][2] = {
 };
 std::atomic<int> g_lanes[kFamilies], g_waves[kFamilies];       // 0 = built-in choice
 
-// `streams` = buffers a lane reads in this call, `tuned_streams` = the number the built-in cap
-// was measured with: a lane with fewer loads in flight needs proportionally more wavefronts
-// beside it (a lane with more keeps the cap).
-Shape shape_of(int family, bool streamed, int streams = 1, int tuned_streams = 1, int default_lanes = 0)
+// The tuned shapes pay from a certain amount of traffic per call on; below it a call is over
+// before the capped pipeline has filled, and full-size uncapped workgroups are faster (measured
+// per launch, buffers rotated so that nothing is cache-resident: reduce p = 16 at 320 MB 57 us
+// against 61 us, at 640 MB 108 against 103; average r = 8 at 72 MB 14.3 against 15.9, at 576 MB
+// 100 against 94; fused at 116 MB 22.4 against 24.8, at 464 MB 89 against 75; reorder at 32 MB
+// 7.7 against 8.7, at 64 MB 13.1 against 12.0; Adam: no difference below 100 MB).
+constexpr size_t kTunedFromBytes[kFamilies] = {48u << 20, 448u << 20, 256u << 20, 0, 200u << 20};
+constexpr Shape kSmallCallShape = {512, 0};
+
+// `traffic` = algorithmic bytes of the call; `streams` = buffers a lane reads in this call,
+// `tuned_streams` = the number the built-in cap was measured with: a lane with fewer loads in
+// flight needs proportionally more wavefronts beside it (a lane with more keeps the cap).
+Shape shape_of(int family, bool streamed, size_t traffic, int streams = 1, int tuned_streams = 1,
+               int default_lanes = 0)
 {
     Shape sh = kDefaultShape[family][streamed ? 1 : 0];
     if (default_lanes) sh.lanes = default_lanes;
     if (sh.waves_per_cu > 0 && streams < tuned_streams)
         sh.waves_per_cu = (sh.waves_per_cu * tuned_streams + streams - 1) / streams;
+    if (traffic < kTunedFromBytes[family]) sh = kSmallCallShape;
     if (const int l = g_lanes[family].load()) sh.lanes = l;
     if (const int w = g_waves[family].load()) sh.waves_per_cu = w;
     if (sh.waves_per_cu >= 32) sh.waves_per_cu = 0;
@@ -1094,7 +1105,7 @@ int launch_reorder(void* dst, const PtrTable& src, size_t n_valid_bytes, size_t 
     if (vec16) {
         // spread the block budget over the p chunks
         unsigned total = 0;
-        const Shape sh = shape_of(kFamReorder, true);
+        const Shape sh = shape_of(kFamReorder, true, 2 * n_valid_bytes);
         if (int e = grid_for(shard_bytes / 16 * (size_t)p, sh.lanes, MICS_REORDER_BPC, &total)) return e;
         unsigned bx = (total + (unsigned)p - 1) / (unsigned)p;
         return launch(reorder_vec_kernel, dim3(bx, (unsigned)p), dim3(sh.lanes), lds_for(sh), st, (u32x4*)dst, src,
@@ -1136,17 +1147,21 @@ int rsa_launch_kind(float* acc, const PtrTable& g, int p, unsigned lead, size_t 
     }
     const size_t nlanes = (lead + count + 4 * PD - 1) / (4 * PD);
     const bool streamed = stream_acc(count);
-    Shape sh = shape_of(kFamReduce, streamed, p + 2, 18);
+    const size_t traffic = count * ((size_t)GradFormat<KIND>::kElemBytes * (size_t)p + 8);
+    Shape sh = shape_of(kFamReduce, streamed, traffic, p + 2, 18);
     // Single-wavefront workgroups are the fastest when every access is 16-byte aligned; with the
     // accumulator or the gradients off that alignment full-size workgroups are (6070 against
-    // 5740 GB/s at 50 M elements), unless the call is too small to give every compute unit one
-    // (a unit moves about 100 GB/s on its own).
+    // 5740 GB/s at 50 M elements).  A call too small to give every compute unit half a
+    // full-size workgroup runs in single wavefronts in any case, uncapped (a unit moves about
+    // 100 GB/s on its own: 0.5 M elements at p = 16 take 5.3 us instead of 6.2).
     int cus = 0;
     if (int e = compute_units(&cus)) return e;
     bool aligned16 = lead == 0 && ((uintptr_t)acc & 15) == 0;
     for (int q = 0; q < p && aligned16; ++q) aligned16 = ((uintptr_t)g.ptr[q] & 15) == 0;
-    if (!aligned16 && g_lanes[kFamReduce].load() == 0 && nlanes >= (size_t)MICS_RSA_UNALIGNED_BLOCK * (size_t)cus)
-        sh = Shape{MICS_RSA_UNALIGNED_BLOCK, 0};
+    if (g_lanes[kFamReduce].load() == 0) {
+        if (nlanes * 2 <= (size_t)kMaxBlock * (size_t)cus) sh = Shape{64, 0};
+        else if (!aligned16) sh = Shape{MICS_RSA_UNALIGNED_BLOCK, 0};
+    }
     // binary16 gradients cost a conversion per element: the arithmetic then needs every wavefront
     // that fits (p = 16, 50 M elements: 6430 GB/s uncapped, 4450 with 10 wavefronts per unit)
     if (KIND == 1 && g_waves[kFamReduce].load() == 0) sh.waves_per_cu = 0;
@@ -1204,7 +1219,7 @@ int launch_replica_average(float* out, const PtrTable& a, size_t count, int r, f
     hipStream_t st = (hipStream_t)stream;
     unsigned blocks = 0;
     const bool streamed = stream_acc(count);
-    const Shape sh = shape_of(kFamAverage, streamed, r + 1, 9);
+    const Shape sh = shape_of(kFamAverage, streamed, count * (4 * (size_t)r + 4), r + 1, 9);
     const size_t lds = lds_for(sh);
     if (int e = grid_for((count + 3) / 4, sh.lanes, MICS_AVG_BPC, &blocks)) return e;
     const dim3 gr(blocks), bl(sh.lanes);
@@ -1224,7 +1239,7 @@ int launch_adam(float* master, float* exp_avg, float* exp_avg_sq, uint16_t* para
 {
     hipStream_t st = (hipStream_t)stream;
     unsigned blocks = 0;
-    const Shape sh = shape_of(kFamAdam, stream_acc(count));
+    const Shape sh = shape_of(kFamAdam, stream_acc(count), count * 30);
     if (int e = grid_for((count + 3) / 4, sh.lanes, MICS_ADAM_BPC, &blocks)) return e;
     if (param_bf16)
         return launch(adam_kernel<true>, dim3(blocks), dim3(sh.lanes), lds_for(sh), st, master, exp_avg, exp_avg_sq,
@@ -1242,7 +1257,9 @@ int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs
         const int nt = n - first < kMaxSeg ? n - first : kMaxSeg;
         size_t tiles = 0;
         if (vec16) {
-            const Shape sh = shape_of(kFamReorder, true, 1, 1, kSegLanes);
+            size_t moved = 0;
+            for (int t = 0; t < nt; ++t) moved += 2 * segs[first + t].numel * eb;
+            const Shape sh = shape_of(kFamReorder, true, moved, 1, 1, kSegLanes);
             const size_t tile_vecs = (size_t)sh.lanes * MICS_SEG_U;
             ReorderSegTable tab;
             tab.n = nt;
@@ -1263,7 +1280,7 @@ int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs
                 return e;
         } else {
             // fixed 256-lane tiles; the family's cap on wavefronts per compute unit applies
-            const Shape lds_shape = {kBlock, shape_of(kFamReorder, true, 1, 1, kBlock).waves_per_cu};
+            const Shape lds_shape = {kBlock, shape_of(kFamReorder, true, (size_t)1 << 40, 1, 1, kBlock).waves_per_cu};
             const size_t lds_cap = lds_for(lds_shape);
             if (nt == 1) {
                 const Segment& sg = segs[first];
@@ -1317,7 +1334,7 @@ int launch_reduce_coalesced(float* acc, const PtrTable& grads, const Segment* se
         const bool streamed = stream_acc(elements);
         // as in rsa_launch_kind: single-wavefront workgroups if every access is 16-byte aligned
         // (h = 8192 layer: 6460 against 6220 GB/s), full-size ones otherwise
-        Shape sh = shape_of(kFamReduce, streamed, p + 2, 18);
+        Shape sh = shape_of(kFamReduce, streamed, elements * (2 * (size_t)p + 8), p + 2, 18);
         bool aligned16 = base_lead == 0 && ((uintptr_t)acc & 15) == 0;
         for (int q = 0; q < p && aligned16; ++q) aligned16 = ((uintptr_t)g.ptr[q] & 15) == 0;
         for (int t = 0; t < tab.n && aligned16; ++t)
@@ -1365,7 +1382,7 @@ int launch_avg_adam(float* master, float* exp_avg, float* exp_avg_sq, uint16_t* 
 {
     hipStream_t st = (hipStream_t)stream;
     unsigned blocks = 0;
-    const Shape sh = shape_of(kFamFused, stream_acc(count), r + 3, 11);
+    const Shape sh = shape_of(kFamFused, stream_acc(count), count * (4 * (size_t)r + 26), r + 3, 11);
     const size_t lds = lds_for(sh);
     if (int e = grid_for((count + 3) / 4, sh.lanes, MICS_ADAM_BPC, &blocks)) return e;
     return dispatch2(param_bf16 != nullptr, false, [&](auto BF, auto) {
