@@ -73,6 +73,9 @@ def parse_args():
                     help="launch shape of a kernel family (reorder, reduce, average, adam, fused): lanes per "
                          "workgroup and wavefronts per compute unit, 0 = built-in choice (mics_set_launch_shape); "
                          "may be given several times")
+    ap.add_argument("--stream-threshold-mb", type=int, default=0,
+                    help="outputs larger than this are streamed past the caches; 0 = the library's default of "
+                         "224 (mics_set_stream_threshold_bytes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-group-view", action="store_true",
                     help="skip the whole-group view that follows the rank-view steps")
@@ -385,6 +388,7 @@ class Workload:
                             + (", coalesced: 16 separately sharded tensors" if a.coalesced else ""),
                 "view": self.view, "coalesced": bool(a.coalesced), "fused_average_adam": bool(a.fused),
                 "adam_writes_stage1_buffer": bool(a.stage1_out), "launch_shape_overrides": list(a.launch_shape),
+                "stream_threshold_mb_override": a.stream_threshold_mb,
                 "gathers_per_microstep": a.gathers_per_microstep, "N": N, "S": self.S, "p": p, "k": k, "r": r, "s": s,
                 "algorithmic_bytes_per_step": b_step,
                 "accumulator_bytes": 4 * count,
@@ -437,6 +441,8 @@ def main():
     torch.cuda.set_device(torch.device("cuda:0"))
     if args.blocks_per_cu:
         mics.mics_set_blocks_per_cu(args.blocks_per_cu)
+    if args.stream_threshold_mb:
+        mics.mics_set_stream_threshold_bytes(args.stream_threshold_mb << 20)
     families = {"reorder": mics.MICS_KERNELS_REORDER, "reduce": mics.MICS_KERNELS_REDUCE,
                 "average": mics.MICS_KERNELS_AVERAGE, "adam": mics.MICS_KERNELS_ADAM, "fused": mics.MICS_KERNELS_FUSED}
     for spec in args.launch_shape:

@@ -23,10 +23,11 @@ int mics_set_blocks_per_cu(int blocks_per_cu);
 
 /*
  * The reduce and average kernels leave an accumulator / output of up to `bytes` bytes
- * cacheable and stream a larger one past the caches with non-temporal accesses (default
- * 224 MiB: what the 256 MB Infinity Cache of an MI355X absorbs).  0 restores the default;
- * 1 makes every call take the streaming kernels, which is how the tests reach them with
- * small buffers.  Returns MICS_OK.
+ * cacheable and stream a larger one past the caches with non-temporal accesses.  0 restores
+ * the built-in policy (224 MiB -- what the 256 MB Infinity Cache of an MI355X absorbs -- and,
+ * for reductions over 32 or more buffers, always streamed); 1 makes every call take the
+ * streaming kernels and a huge value none, which is how the tests reach both kinds with small
+ * buffers.  Returns MICS_OK.
  */
 int mics_set_stream_threshold_bytes(size_t bytes);
 

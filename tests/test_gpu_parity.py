@@ -750,14 +750,16 @@ def test_adam_writes_bf16_in_stage1_layout_of_the_next_gather(orc, gen, p, k, S,
 
 # ---- accumulators and outputs larger than the cache: the streaming kernels ------------------------------
 
-def test_streaming_kernels_give_the_same_results(orc, gen):
-    """Accumulators (reduce) and outputs (average) above 224 MiB take kernels with non-temporal
-    accumulator accesses.  With the threshold at one byte every call here takes them: flat, odd
-    offsets, unrolled and any-p groups, small messages, fp16 / fp32 gradients, the coalesced form,
-    unrolled and any-r averages."""
+@pytest.mark.parametrize("threshold", [1, 1 << 40], ids=["all-streamed", "none-streamed"])
+def test_streaming_kernels_give_the_same_results(orc, gen, threshold):
+    """Accumulators (reduce) and outputs (average) above 224 MiB, and the accumulators of groups of
+    32 and more, take kernels with non-temporal accumulator accesses.  With the threshold at one
+    byte every call here takes them, with a huge one none does: flat, odd offsets, unrolled and
+    any-p groups, small messages, fp16 / fp32 gradients, the coalesced form, unrolled and any-r
+    averages."""
     tab = gen.normal_table(1e-3, "bf16")
     try:
-        mics.mics_set_stream_threshold_bytes(1)
+        mics.mics_set_stream_threshold_bytes(threshold)
         for p, off, count in [(16, 0, 40003), (2, 1, 30000), (1, 0, 5000), (4, 3, 9000), (8, 0, 20000),
                               (32, 0, 140000), (37, 5, 30000), (64, 1, 8000), (16, 8, 1100000)]:
             total = off + count + 3
@@ -788,7 +790,7 @@ def test_streaming_kernels_give_the_same_results(orc, gen):
                 assert np.array_equal(acc.numpy().view(np.uint32), ref.view(np.uint32)), (name, p, off)
                 assert acc.guards_intact()
         for p, k, numels, align in [(16, 8, [512 * 16, 16 * 40000, 16 * 8], 8), (8, 8, [1000, 77, 5000, 3], 1),
-                                    (3, 3, [30000, 24], 8)]:
+                                    (3, 3, [30000, 24], 8), (32, 8, [32 * 3000, 64, 32 * 500 + 7], 8)]:
             lay = gen.coalesced_layout(numels, p, k, align=align)
             total = lay.grad_off[-1]
             segs = lay.reduce_segments(p - 1)
