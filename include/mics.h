@@ -50,7 +50,7 @@
  *     that bf16/fp16 gradient buffers of one call should all start at even or
  *     all at odd element addresses (otherwise about 20 % slower).  The reorder
  *     runs at copy speed when every buffer and the shard size are multiples
- *     of 16 bytes and through an LDS-staged kernel (about 10 % slower) otherwise.
+ *     of 16 bytes and through a re-phasing kernel (about 8 % slower) otherwise.
  *   - Buffers of one call must not overlap unless stated.
  */
 #ifndef MICS_H

@@ -346,7 +346,7 @@ int mics_hier_gather_reorder_coalesced(void* dst_flat, const void* const* stage1
                              fn, bad_a, bad_b);
 
     // Tensors whose bases, shard size and offsets are 16-byte clean go to the vector kernel, all
-    // others to the LDS-staged kernel: one launch per kMaxSegPerLaunch tensors of either kind.
+    // others to the kernel for any alignment: one launch per kMaxSegPerLaunch tensors of either kind.
     mics::Segment clean[mics::kMaxSegPerLaunch], other[mics::kMaxSegPerLaunch];
     int nc = 0, no = 0;
     for (int t = 0; t <= n_segs; ++t) {

@@ -21,7 +21,7 @@ struct PtrTable {
 // kMaxSegPerLaunch segments.
 
 // vec16: every source, the destination and the shard size are multiples of 16
-// bytes -> direct 128-bit copy; otherwise the LDS-staged re-phasing kernel.
+// bytes -> direct 128-bit copy; otherwise the kernel that re-phases through a lane shift.
 int launch_reorder(void* dst, const PtrTable& src, size_t n_valid_bytes,
                    size_t shard_bytes, int p, int k, bool vec16, void* stream);
 
@@ -57,7 +57,7 @@ struct Segment {
 };
 
 // vec16: every segment satisfies the 16-byte conditions of the vector kernel (bases, shard
-// size and both offsets); otherwise the segments go through the LDS-staged kernel, which
+// size and both offsets); otherwise the segments go through the lane-shift kernel, which
 // takes any element-aligned geometry.
 int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs, int n, int p,
                              int k, int elem_bytes, bool vec16, void* stream);

@@ -63,12 +63,6 @@ typedef f32x2 f32x2_a4 __attribute__((aligned(4)));
 #ifndef MICS_REORDER_NTS
 #define MICS_REORDER_NTS 1
 #endif
-#ifndef MICS_LDS_NTL
-#define MICS_LDS_NTL 1
-#endif
-#ifndef MICS_LDS_NTS
-#define MICS_LDS_NTS 1
-#endif
 #ifndef MICS_RSA_BLOCK
 #define MICS_RSA_BLOCK 64
 #endif
@@ -160,7 +154,6 @@ typedef f32x2 f32x2_a4 __attribute__((aligned(4)));
 #define MICS_NARROW_MIN_P 40
 #endif
 
-constexpr int kBlock = 256;              // LDS reorder
 constexpr int kMaxBlock = 512;           // most lanes per workgroup of the element-wise kernels
 constexpr int kNarrowBlock = MICS_NARROW_BLOCK;
 constexpr bool kReorderNtl = MICS_REORDER_NTL, kReorderNts = MICS_REORDER_NTS;
@@ -343,29 +336,18 @@ __global__ __launch_bounds__(kMaxBlock) void reorder_seg_kernel(
 
 // General case: source and destination of a chunk sit at different offsets
 // within their 16-byte lines (odd shard sizes, sub-buffers that start anywhere
-// on an element boundary).  A workgroup stages the source bytes of one
-// destination tile in LDS with aligned 128-bit loads, then every lane rebuilds
-// its aligned 128-bit destination vector from two LDS vectors shifted by the
-// (workgroup-uniform) phase.  The partial vectors at the two ends of a chunk
-// are moved in 2-byte units.  Global memory is touched only inside the chunk.
-// Like reorder_seg_kernel the kernel serves many tensors per launch: workgroup x
-// moves tile x - tile_begin[t] of chunk blockIdx.y of tensor t.
-#ifndef MICS_LDS_VECS_PER_LANE
-#define MICS_LDS_VECS_PER_LANE 4
-#endif
-constexpr int kStageVecsPerThread = MICS_LDS_VECS_PER_LANE;
-constexpr int kTileVecs = kBlock * kStageVecsPerThread;   // destination vectors per tile
-constexpr int kTileBytes = kTileVecs * 16;
-
-struct LdsSeg {
+// on an element boundary).  Like reorder_seg_kernel the kernel serves many
+// tensors per launch: workgroup x moves tile x - tile_begin[t] of chunk
+// blockIdx.y of tensor t.
+struct ByteSeg {
     unsigned long long shard_bytes, valid_bytes, src_byte, dst_byte;
 };
 // Where workgroup x works: many tensors (table in the kernel arguments) ...
-struct LdsSegTable {
+struct ByteSegTable {
     int n;
     unsigned tile_begin[kMaxSeg + 1];
-    LdsSeg seg[kMaxSeg];
-    __device__ __forceinline__ const LdsSeg& locate(unsigned x, size_t* tile) const
+    ByteSeg seg[kMaxSeg];
+    __device__ __forceinline__ const ByteSeg& locate(unsigned x, size_t* tile) const
     {
         const int t = segment_of(tile_begin, x);
         *tile = x - tile_begin[t];
@@ -373,22 +355,41 @@ struct LdsSegTable {
     }
 };
 // ... or a single tensor: no table, no look-up (4 % faster than a table of one entry).
-struct LdsOneTensor {
-    LdsSeg seg;
-    __device__ __forceinline__ const LdsSeg& locate(unsigned x, size_t* tile) const
+struct OneTensor {
+    ByteSeg seg;
+    __device__ __forceinline__ const ByteSeg& locate(unsigned x, size_t* tile) const
     {
         *tile = x;
         return seg;
     }
 };
 
+// Destination vectors are written aligned.  gfx950 executes a 128-bit load at any 4-byte
+// aligned address at full speed, so a chunk whose source is a multiple of 4 bytes off its
+// destination's 16-byte grid is a plain copy with under-aligned loads.  Otherwise (2 bytes off, odd shard sizes of
+// 2-byte elements) a lane loads the 16 bytes from 2 bytes before its source -- 4-byte aligned --
+// and takes the last 2 bytes it needs from the next lane's first dword through a lane shift;
+// only the last lane of a wavefront (or of the chunk) loads those 2 bytes itself.  The phase
+// is the same for every vector of a chunk, so the branches are workgroup-uniform.  Partial
+// vectors at the two ends of a chunk go in 2-byte units on lanes 0 .. 15 of the chunk's first
+// workgroup.  Global memory is touched only inside the chunk.  (An earlier form staged every
+// tile in LDS and rebuilt the vectors from two LDS reads: 5.2 TB/s on the layer with odd shards
+// where this one reaches 5.8, and 4.6 against 5.0 with 16 tensors per launch.)
+#ifndef MICS_SHIFT_U
+#define MICS_SHIFT_U 2
+#endif
+#ifndef MICS_SHIFT_BLOCK
+#define MICS_SHIFT_BLOCK 256     // 64 lanes: 5.40 TB/s, 128 .. 512: 5.76 .. 5.84
+#endif
+#ifndef MICS_SHIFT_NTL
+#define MICS_SHIFT_NTL 1
+#endif
 template <typename Where>
-__global__ __launch_bounds__(kBlock) void reorder_lds_kernel(
+__global__ __launch_bounds__(kMaxBlock) void reorder_shift_kernel(
     unsigned char* __restrict__ dst, PtrTable src, Where where, int k)
 {
-    __shared__ u32x4 stage[kTileVecs + 2];
     size_t tile;
-    const LdsSeg& sg = where.locate(blockIdx.x, &tile);
+    const ByteSeg& sg = where.locate(blockIdx.x, &tile);
     const size_t shard_bytes = sg.shard_bytes, n_valid_bytes = sg.valid_bytes;
     const size_t g = blockIdx.y;
     const size_t chunk_begin = g * shard_bytes;
@@ -400,62 +401,50 @@ __global__ __launch_bounds__(kBlock) void reorder_lds_kernel(
     const uintptr_t d_lo = (uintptr_t)dst + sg.dst_byte + chunk_begin;      // chunk in dst
     const uintptr_t d_hi = d_lo + valid;
     const uintptr_t s_chunk = (uintptr_t)src.ptr[l] + sg.src_byte + j * shard_bytes;
-    const uintptr_t grid0 = d_lo & ~(uintptr_t)15;                     // 16-byte grid of dst
-    const size_t ntiles = (d_hi - grid0 + kTileBytes - 1) / kTileBytes;
-    if (tile >= ntiles) return;                                         // uniform per workgroup
-    const unsigned phase = (unsigned)((s_chunk - d_lo) & 15);           // even, uniform
-    const unsigned dshift = phase >> 2, half = (phase >> 1) & 1;
-    const uint16_t* stage_h = (const uint16_t*)stage;
+    const uintptr_t a_lo = (d_lo + 15) & ~(uintptr_t)15;                    // first full dst vector
+    const size_t nfull = a_lo + 16 <= d_hi ? ((d_hi & ~(uintptr_t)15) - a_lo) / 16 : 0;
 
-    const uintptr_t tile0 = grid0 + tile * kTileBytes;
-    const uintptr_t t_lo = tile0 > d_lo ? tile0 : d_lo;
-    const uintptr_t t_hi = tile0 + kTileBytes < d_hi ? tile0 + kTileBytes : d_hi;
-    const uintptr_t s_lo = s_chunk + (t_lo - d_lo), s_hi = s_chunk + (t_hi - d_lo);
-    const uintptr_t sa = s_lo & ~(uintptr_t)15;
-    const unsigned nsv = (unsigned)(((s_hi + 15) & ~(uintptr_t)15) - sa) / 16;   // <= kTileVecs+1
-
-    for (unsigned v = threadIdx.x; v < nsv; v += kBlock) {
-        const uintptr_t a = sa + (uintptr_t)v * 16;
-        if (a >= s_lo && a + 16 <= s_hi) {
-            stage[v] = MICS_LD(MICS_LDS_NTL, (const u32x4*)a);
-        } else {
-            uint16_t* row = (uint16_t*)&stage[v];
-            for (unsigned h = 0; h < 8; ++h) {
-                const uintptr_t b = a + 2 * h;
-                if (b >= s_lo && b < s_hi) row[h] = *(const uint16_t*)b;
-            }
-        }
+    if (tile == 0 && threadIdx.x < 16) {
+        const uintptr_t head_end = a_lo < d_hi ? a_lo : d_hi;
+        const uintptr_t b = threadIdx.x < 8 ? d_lo + 2 * threadIdx.x
+                                            : a_lo + nfull * 16 + 2 * (threadIdx.x - 8);
+        const bool on = threadIdx.x < 8 ? b < head_end : (b >= head_end && b < d_hi);
+        if (on) *(uint16_t*)b = *(const uint16_t*)(s_chunk + (b - d_lo));
     }
-    __syncthreads();
+    const size_t i0 = tile * ((size_t)blockDim.x * MICS_SHIFT_U);
+    if (i0 >= nfull) return;                                                // workgroup-uniform
+    const uintptr_t s_lo = s_chunk + (a_lo - d_lo);                         // source of full vector 0
+    const bool odd = (s_lo & 2) != 0;                                       // chunk-uniform
 
-    for (unsigned vv = threadIdx.x; vv < kTileVecs; vv += kBlock) {
-        const uintptr_t a = tile0 + (uintptr_t)vv * 16;      // aligned dst address
-        if (a + 16 <= t_lo || a >= t_hi) continue;
-        // byte offset of this vector's source bytes inside the staged range
-        const long o = (long)(a - d_lo) + (long)(s_chunk - sa);   // a may lie below d_lo
-        if (a >= t_lo && a + 16 <= t_hi) {
-            const unsigned o16 = (unsigned)o >> 4;
-            const u32x4 lo = stage[o16], hi = stage[o16 + 1];
-            // shift the 8 staged dwords down by `dshift` dwords (uniform), then by
-            // half a dword if the phase is an odd number of 2-byte units
-            uint32_t w0 = lo.x, w1 = lo.y, w2 = lo.z, w3 = lo.w;
-            uint32_t w4 = hi.x, w5 = hi.y, w6 = hi.z, w7 = hi.w;
-            if (dshift & 1) { w0 = w1; w1 = w2; w2 = w3; w3 = w4; w4 = w5; w5 = w6; w6 = w7; }
-            if (dshift & 2) { w0 = w2; w1 = w3; w2 = w4; w3 = w5; w4 = w6; }
-            u32x4 out = {w0, w1, w2, w3};
-            if (half) {
-                out.x = (w0 >> 16) | (w1 << 16);
-                out.y = (w1 >> 16) | (w2 << 16);
-                out.z = (w2 >> 16) | (w3 << 16);
-                out.w = (w3 >> 16) | (w4 << 16);
-            }
-            MICS_ST(MICS_LDS_NTS, (u32x4*)a, out);
+    #pragma unroll
+    for (int u = 0; u < MICS_SHIFT_U; ++u) {
+        const size_t i = i0 + (size_t)u * blockDim.x + threadIdx.x;
+        const bool has = i < nfull;
+        const uintptr_t s = s_lo + 16 * i;
+        u32x4 out = {0, 0, 0, 0};
+        if (!odd) {
+            if (has) out = MICS_LD(MICS_SHIFT_NTL, (const u32x4_a4*)s);
         } else {
-            for (unsigned h = 0; h < 8; ++h) {
-                const uintptr_t b = a + 2 * h;
-                if (b >= t_lo && b < t_hi) *(uint16_t*)b = stage_h[(o + 2 * (long)h) >> 1];
+            // vector 0 of a chunk whose destination starts on a 16-byte line has nothing in
+            // front of it inside the chunk: that one lane loads from its 2-byte aligned source
+            const bool direct = s - 2 < s_chunk;
+            u32x4 w = {0, 0, 0, 0};
+            if (has) {
+                if (direct) w = MICS_LD(MICS_SHIFT_NTL, (const u32x4_a2*)s);
+                else w = MICS_LD(MICS_SHIFT_NTL, (const u32x4_a4*)(s - 2));
+            }
+            uint32_t next = (uint32_t)__shfl_down((int)w.x, 1);             // every lane takes part
+            if (has && ((threadIdx.x & 63u) == 63u || i + 1 >= nfull)) next = *(const uint16_t*)(s + 14);
+            if (direct) {
+                out = w;
+            } else {
+                out.x = (w.x >> 16) | (w.y << 16);
+                out.y = (w.y >> 16) | (w.z << 16);
+                out.z = (w.z >> 16) | (w.w << 16);
+                out.w = (w.w >> 16) | (next << 16);
             }
         }
+        if (has) MICS_ST(kReorderNts, (u32x4*)(a_lo + 16 * i), out);
     }
 }
 
@@ -1293,25 +1282,31 @@ int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs
                                (u32x4*)dst, src, tab, k))
                 return e;
         } else {
-            // fixed 256-lane tiles; the family's cap on wavefronts per compute unit applies
-            const Shape lds_shape = {kBlock, shape_of(kFamReorder, true, (size_t)1 << 40, 1, 1, kBlock).waves_per_cu};
-            const size_t lds_cap = lds_for(lds_shape);
+            size_t moved = 0;
+            for (int t = 0; t < nt; ++t) moved += 2 * segs[first + t].numel * eb;
+            const Shape sh = shape_of(kFamReorder, true, moved, 1, 1, MICS_SHIFT_BLOCK);
+            const size_t tile_bytes = (size_t)sh.lanes * MICS_SHIFT_U * 16;
+            // tiles of full destination vectors; at least one per tensor, for the chunk ends
+            auto tiles_of = [&](const ByteSeg& sg) {
+                const size_t t = (sg.shard_bytes + tile_bytes - 1) / tile_bytes;
+                return sg.valid_bytes ? (t ? t : 1) : 0;
+            };
             if (nt == 1) {
                 const Segment& sg = segs[first];
-                LdsOneTensor one;
+                OneTensor one;
                 one.seg.shard_bytes = sg.shard_elems * eb;
                 one.seg.valid_bytes = sg.numel * eb;
                 one.seg.src_byte = sg.src_offset * eb;
                 one.seg.dst_byte = sg.dst_offset * eb;
-                tiles = sg.numel ? (one.seg.shard_bytes + 15 + kTileBytes - 1) / kTileBytes : 0;
+                tiles = tiles_of(one.seg);
                 if (tiles > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
                 if (tiles == 0) continue;
-                if (int e = launch(reorder_lds_kernel<LdsOneTensor>, dim3((unsigned)tiles, (unsigned)p), dim3(kBlock), lds_cap, st,
-                                   (unsigned char*)dst, src, one, k))
+                if (int e = launch(reorder_shift_kernel<OneTensor>, dim3((unsigned)tiles, (unsigned)p), dim3(sh.lanes),
+                                   lds_for(sh), st, (unsigned char*)dst, src, one, k))
                     return e;
                 continue;
             }
-            LdsSegTable tab;
+            ByteSegTable tab;
             tab.n = nt;
             for (int t = 0; t < nt; ++t) {
                 const Segment& sg = segs[first + t];
@@ -1320,14 +1315,13 @@ int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs
                 tab.seg[t].valid_bytes = sg.numel * eb;
                 tab.seg[t].src_byte = sg.src_offset * eb;
                 tab.seg[t].dst_byte = sg.dst_offset * eb;
-                // a chunk of shard_bytes that starts up to 15 bytes into the destination's 16-byte grid
-                if (sg.numel) tiles += (tab.seg[t].shard_bytes + 15 + kTileBytes - 1) / kTileBytes;
+                tiles += tiles_of(tab.seg[t]);
                 if (tiles > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
             }
             for (int t = nt; t <= kMaxSeg; ++t) tab.tile_begin[t] = 0xFFFFFFFFu;
             if (tiles == 0) continue;
-            if (int e = launch(reorder_lds_kernel<LdsSegTable>, dim3((unsigned)tiles, (unsigned)p), dim3(kBlock), lds_cap, st,
-                               (unsigned char*)dst, src, tab, k))
+            if (int e = launch(reorder_shift_kernel<ByteSegTable>, dim3((unsigned)tiles, (unsigned)p), dim3(sh.lanes),
+                               lds_for(sh), st, (unsigned char*)dst, src, tab, k))
                 return e;
         }
     }

@@ -39,12 +39,15 @@ REORDER_CASES = [
     (8, 1, 1000, 4, -1, 0, 0),                # one device per node
     (32, 8, 2056, 2, -13, 0, 0),              # cfg-4 geometry with 13 padded elements
     (12, 4, 8, 2, None, 0, 0),                # chunks of one vector
-    (6, 3, 4099, 2, None, 0, 0),              # odd shard: LDS re-phasing path
+    (6, 3, 4099, 2, None, 0, 0),              # odd shard: re-phasing path
     (6, 3, 4099, 4, -7, 0, 0),
     (4, 2, 70001, 2, -2, 0, 0),               # odd shard spanning several tiles
     (4, 2, 4096, 2, None, 3, 0),              # aligned shard, sources off by 6 bytes
     (4, 2, 4096, 2, None, 0, 5),              # destination off by 10 bytes
     (16, 8, 777, 2, -100, 1, 7),              # everything misaligned
+    (4, 2, 40000, 2, None, 1, 0),             # chunks start on 16-byte lines, sources 2 bytes off: the lane shift
+    (4, 2, 40000, 2, -3, 2, 0),               # sources 4 bytes off: under-aligned loads only
+    (8, 2, 33333, 2, -1, 0, 3),               # odd shard, destination 6 bytes off: both kinds of chunk
     (16, 8, 5, 2, None, 1, 1),                # chunks smaller than a vector
     (3, 3, 1, 2, None, 0, 0),
     (1, 1, 12345, 4, None, 0, 0),
@@ -836,6 +839,13 @@ def test_launch_shapes_give_the_same_results(orc, gen, lanes, waves):
         mics.mics_hier_gather_reorder(dst.t, [upload(t) for t in T], n, S, p, k, 2)
         torch.cuda.synchronize()
         assert np.array_equal(dst.numpy()[:n], orc.concat_shards(shards, n)) and dst.guards_intact()
+        # sources 2 and 6 bytes off the destination's 16-byte grid: the lane-shift kernel
+        for skew in (1, 3):
+            T_skew = [Guarded(t.size, np.uint16, skew=skew, fill=t) for t in T]
+            dst = Guarded(p * S, np.uint16)
+            mics.mics_hier_gather_reorder(dst.t, [t.t for t in T_skew], n, S, p, k, 2)
+            torch.cuda.synchronize()
+            assert np.array_equal(dst.numpy()[:n], orc.concat_shards(shards, n)) and dst.guards_intact()
         for threshold in (0, 1):                       # cacheable, then streamed accumulators
             mics.mics_set_stream_threshold_bytes(threshold)
             for off in (0, 3):
