@@ -217,7 +217,8 @@ class Workload:
                          tab_p, pb)
             self.reorder_segs = mics._segments(lay.reorder_segments())
             # a2: every rank's full gradient buffer (all tensors, p*S_t each); the rank reads its slices
-            n_sets = min(s, 4)
+            # distinct gradient data per micro-step as far as ~120 GB go (every set is far beyond any cache)
+            n_sets = max(1, min(s, 4, int(120e9 // (2 * p * lay.grad_off[-1]))))
             grads = torch.empty((n_sets, p, -(-lay.grad_off[-1] // 8) * 8), dtype=torch.int16, device=dev)
             for t in range(n_sets):
                 for q in range(p):
@@ -382,7 +383,10 @@ class Workload:
             "ms_per_step_events": {key: round(val, 4) for key, val in st_step.items()},
             "elements_per_s": round(count / (ms_step * 1e-3), 1),
             "config": {
-                "workload": f"{cfg.name}: one transformer layer h={cfg.name[1:]} N={N}, p={p} "
+                "workload": f"{cfg.name}: "
+                            + (f"one transformer layer h={cfg.name[1:].split('_')[0]} " if cfg.name != "tiny"
+                               else "flat buffer ")
+                            + f"N={N}, p={p} "
                             f"({p // k} nodes x k={k}), r={r}, s={s}, {self.view} view "
                             f"({count} elements per reduce/average/Adam call)"
                             + (", coalesced: 16 separately sharded tensors" if a.coalesced else ""),

@@ -92,6 +92,9 @@ CONFIGS = {
     "h5120_odd": Config("h5120_odd", layer_elems(5120) + 5, p=32, k=8, r=2, s=4, sigma_grad=1e-3,
                         seed=1004, outlier_frac=0.01, align=1),
     "h8192": Config("h8192", layer_elems(8192), p=16, k=8, r=8, s=12, sigma_grad=1e-4, seed=1005),
+    # the h = 8192 layer in the partition group the paper trains its 50B model with (8 nodes of
+    # 8 devices, Section 5) and the 4 micro-steps of its large-scale run
+    "h8192_p64": Config("h8192_p64", layer_elems(8192), p=64, k=8, r=2, s=4, sigma_grad=1e-4, seed=1006),
 }
 
 

@@ -91,7 +91,7 @@ def test_device_generator_matches_host_twin(gen):
     assert abs(float(w.std()) / cfg.sigma_master - 1) < 0.01 and abs(float(w.mean())) < 1e-4
 
 
-@pytest.mark.parametrize("name", ["h2560", "h4096", "h5120", "h5120_odd", "h8192"])
+@pytest.mark.parametrize("name", ["h2560", "h4096", "h5120", "h5120_odd", "h8192", "h8192_p64"])
 def test_reorder_full_size(orc, gen, name):
     cfg = gen.CONFIGS[name]
     p, k, S, N, n_pad = cfg.p, cfg.k, cfg.S, cfg.N, cfg.N_pad
@@ -201,7 +201,7 @@ def run_rank_pipeline(orc, gen, cfg, rank, count, offset, boundaries=()):
 
 
 @pytest.mark.parametrize("name,rank", [("h2560", 3), ("h4096", 15), ("h5120", 31), ("h5120_odd", 7),
-                                       ("h8192", 5)])
+                                       ("h8192", 5), ("h8192_p64", 41)])
 def test_rank_view_pipeline_full_size(orc, gen, name, rank):
     cfg = gen.CONFIGS[name]
     assert run_rank_pipeline(orc, gen, cfg, rank, cfg.S, rank * cfg.S) >= min(cfg.S // 100, 6 * WIN)
