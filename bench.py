@@ -329,6 +329,14 @@ class Workload:
             self.step(it, True)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
+        # the same steps once more without the per-kernel event marks (each mark is a packet of its
+        # own on the stream: about 4 us, which shows on the small configurations); reported beside
+        # `value`, never instead of it
+        t0 = time.perf_counter()
+        for it in range(warmup + steps + 1, warmup + 2 * steps + 1):
+            self.step(it, False)
+        torch.cuda.synchronize()
+        self.wall_unmarked = time.perf_counter() - t0
         return self.record(steps, warmup, wall)
 
     def record(self, steps, warmup, wall):
@@ -381,6 +389,11 @@ class Workload:
             "data": "synthetic",
             "pct_of_peak_hbm": round(100.0 * gbps / PEAK_HBM_GBPS, 2),
             "ms_per_step_events": {key: round(val, 4) for key, val in st_step.items()},
+            "without_kernel_event_marks": {
+                "ms_per_step": round(self.wall_unmarked * 1e3 / steps, 4),
+                "value": round(b_step / (self.wall_unmarked / steps) / 1e9, 1),
+                "note": "the same number of steps after the timed region, no events between the kernels",
+            },
             "elements_per_s": round(count / (ms_step * 1e-3), 1),
             "config": {
                 "workload": f"{cfg.name}: "
