@@ -333,6 +333,8 @@ COALESCED_CASES = [
     (8, 8, [1000, 77, 5000, 3], 1, 2),                        # odd shards: every tensor takes the slow path
     (4, 2, [4096, 1001, 8192, 5], 8, 4),                      # fp32 elements, ragged tensors
     (6, 3, [64 * 6] * 60, 8, 2),                              # more tensors than one launch carries
+    (4, 2, [70001, 33, 140003], 1, 2),                        # odd shards spanning several tiles
+    (6, 3, [64 * 6 + 1] * 60, 1, 2),                          # more unaligned tensors than one launch carries
 ]
 
 
@@ -356,6 +358,24 @@ def test_coalesced_reorder_is_bit_exact(orc, gen, p, k, numels, align, eb):
         got = dst.numpy()[lay.flat_off[t]:lay.flat_off[t] + numels[t]]
         assert np.array_equal(got, orc.concat_shards(shards[t], numels[t]))
     assert dst.guards_intact() and all(t.guards_intact() for t in T_dev)
+
+
+def test_one_rank_moves_its_own_chunks_through_the_coalesced_call(orc, gen):
+    """Section 3.3 has every rank rearrange its own stage-1 chunks before the intra-node stage.
+    Rank (j, l) holds T_l = [C_l, C_{k+l}, ...]; its share of the rearrangement -- chunk j' of T_l
+    to position (j'*k + l)*S of the flat buffer -- is p/k plain copies, which the coalesced call
+    takes as p/k one-chunk tensors (p = k = 1).  All k shares together give the whole buffer."""
+    p, k, S = 12, 4, 4099                       # odd shard: the chunks land on every alignment
+    nodes = p // k
+    shards = [tagged(gen, 900 + g, S, np.uint16) for g in range(p)]
+    T = [orc.stage1_gather(shards, k, l) for l in range(k)]
+    dst = Guarded(p * S, np.uint16)
+    T_dev = [upload(t) for t in T]
+    for l in range(k):
+        segs = [(S, S, j * S, (j * k + l) * S) for j in range(nodes)]
+        mics.mics_hier_gather_reorder_coalesced(dst.t, [T_dev[l]], segs, 1, 1, 2)
+    torch.cuda.synchronize()
+    assert np.array_equal(dst.numpy(), orc.concat_shards(shards, p * S)) and dst.guards_intact()
 
 
 @pytest.mark.parametrize("p,k,numels,align", [
