@@ -69,6 +69,8 @@ def _load():
         lib.orc_reduce_scatter_accum_typed.argtypes = [vp, vp, sz, sz, i32, i32, i32]
         lib.orc_f16_widen_array.argtypes = [vp, vp, sz]
         lib.orc_f16_widen_array.restype = None
+        lib.orc_f16_narrow_array.argtypes = [vp, vp, sz]
+        lib.orc_f16_narrow_array.restype = None
         lib.orc_replica_average.argtypes = [vp, vp, sz, i32, f32]
         adam = [vp, vp, vp, vp, vp, sz, f32, f32, f32, f32, f32, i32]
         lib.orc_adam_shard.argtypes = adam
@@ -208,6 +210,14 @@ def f16_widen(h) -> np.ndarray:
     return out
 
 
+def f16_narrow(x) -> np.ndarray:
+    """float32 -> IEEE binary16 bit patterns (uint16), round to nearest even."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape, dtype=np.uint16)
+    _load().orc_f16_narrow_array(_ptr(out), _ptr(x), x.size)
+    return out
+
+
 def reduce_scatter_accum_typed(acc, grads: Sequence[np.ndarray], elem_offset: int, accumulate: bool,
                                dtype: int) -> np.ndarray:
     """reduce_scatter_accum for gradients stored as bf16 / binary16 bit patterns (uint16 arrays)
@@ -253,9 +263,14 @@ def replica_average(copies: Sequence[np.ndarray], scale: float, out=None) -> np.
 # ---- mixed-precision Adam ---------------------------------------------------------
 
 def adam_shard(master, exp_avg, exp_avg_sq, grad, *, lr, beta1, beta2, eps, weight_decay, step,
-               want_bf16: bool = True, f32: bool = False):
-    """In place on master / exp_avg / exp_avg_sq (float32).  Returns the bf16 parameter
-    bit patterns (uint16) or None.  ``f32=True`` selects the strict binary32 variant."""
+               want_bf16: bool = True, f32: bool = False, param_dtype: str = "bf16"):
+    """In place on master / exp_avg / exp_avg_sq (float32).  Returns the low-precision parameter
+    bit patterns (uint16; bf16, or binary16 with ``param_dtype="f16"``: the new master rounded
+    to nearest even) or None.  ``f32=True`` selects the strict binary32 variant."""
+    if param_dtype not in ("bf16", "f16"):
+        raise ValueError("param_dtype must be 'bf16' or 'f16'")
+    as_f16 = want_bf16 and param_dtype == "f16"
+    want_bf16 = want_bf16 and not as_f16
     w, m, v = _c(master, np.float32), _c(exp_avg, np.float32), _c(exp_avg_sq, np.float32)
     g = _c(grad, np.float32)
     count = w.size
@@ -266,4 +281,4 @@ def adam_shard(master, exp_avg, exp_avg_sq, grad, *, lr, beta1, beta2, eps, weig
     _check(fn(_ptr(w), _ptr(m), _ptr(v), _ptr(pb) if pb is not None else None, _ptr(g), count,
               float(np.float32(lr)), float(np.float32(beta1)), float(np.float32(beta2)),
               float(np.float32(eps)), float(np.float32(weight_decay)), int(step)), "adam_shard")
-    return pb
+    return f16_narrow(w) if as_f16 else pb

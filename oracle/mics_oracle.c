@@ -98,6 +98,40 @@ void orc_f16_widen_array(float* out, const uint16_t* in, size_t n)
     for (size_t i = 0; i < n; ++i) out[i] = orc_f16_widen(in[i]);
 }
 
+/* binary32 -> IEEE-754 binary16, round to nearest, ties to even.  binary16 has 10 fraction
+ * bits, exponents -14 .. 15 and subnormals that are multiples of 2^-24. */
+uint16_t orc_f16_narrow(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    const uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+    const uint32_t exp32 = (u >> 23) & 0xFFu;
+    const uint32_t frac32 = u & 0x007FFFFFu;
+    if (exp32 == 0xFFu)                                  /* Inf; NaN stays a (quiet) NaN */
+        return (uint16_t)(sign | 0x7C00u | (frac32 ? 0x0200u | (frac32 >> 13) : 0u));
+    const int e = (int)exp32 - 127;                      /* unbiased exponent of a normal input */
+    if (exp32 == 0 || e < -25) return sign;              /* below half of the smallest subnormal */
+    if (e > 15) return (uint16_t)(sign | 0x7C00u);       /* beyond the largest finite value */
+    /* the 24-bit significand 1.frac32 as an integer, and how many of its low bits do not fit:
+     * 13 for a normal result, more for a subnormal one (whose unit is 2^-24) */
+    const uint32_t sig = frac32 | 0x00800000u;
+    const int drop = e >= -14 ? 13 : 13 + (-14 - e);
+    uint32_t kept = sig >> drop;
+    const uint32_t rest = sig & ((1u << drop) - 1u);
+    const uint32_t half = 1u << (drop - 1);
+    if (rest > half || (rest == half && (kept & 1u))) kept += 1;
+    /* normal: kept holds the hidden bit (bit 10), so adding the biased exponent minus one puts
+     * both in place, and a carry out of the fraction moves into the exponent (up to Inf);
+     * subnormal: kept is the fraction itself, and a carry makes the smallest normal */
+    const uint32_t h = e >= -14 ? ((uint32_t)(e + 15 - 1) << 10) + kept : kept;
+    return (uint16_t)(sign | h);
+}
+
+void orc_f16_narrow_array(uint16_t* out, const float* in, size_t n)
+{
+    for (size_t i = 0; i < n; ++i) out[i] = orc_f16_narrow(in[i]);
+}
+
 /* ---- hierarchical all-gather (Section 3.3) ------------------------------- */
 
 static int geometry_ok(int p, int k, int elem_bytes)

@@ -90,6 +90,10 @@ int orc_reduce_scatter_accum_typed(float* acc, const void* const* grads,
                                    int accumulate, int dtype);
 float orc_f16_widen(uint16_t h);
 void  orc_f16_widen_array(float* out, const uint16_t* in, size_t n);
+/* binary32 -> binary16, round to nearest even, overflow to Inf, subnormals kept: the parameter
+ * format of mixed-precision training on devices without bf16. */
+uint16_t orc_f16_narrow(float f);
+void     orc_f16_narrow_array(uint16_t* out, const float* in, size_t n);
 
 /* Same sum carried in binary64 (every bf16 value and every partial is exact
  * or nearly so): the yardstick that bounds the binary32 error. */

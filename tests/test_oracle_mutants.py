@@ -59,6 +59,12 @@ MUTANTS = [
     ("single-precision Adam divides by the wrong bias correction", "float m_hat = m_new / corr1;",
      "float m_hat = m_new / corr2;", [ADAM]),
     ("binary16 subnormals are off by a factor of two", "(127 - 15 + 1 - shift)", "(127 - 15 - shift)", [DTYPES]),
+    ("binary16 narrowing rounds ties up instead of to even",
+     "if (rest > half || (rest == half && (kept & 1u))) kept += 1;", "if (rest >= half) kept += 1;", [DTYPES]),
+    ("binary16 narrowing truncates", "if (rest > half || (rest == half && (kept & 1u))) kept += 1;", "", [DTYPES]),
+    ("binary16 narrowing drops one bit too few for subnormals", "13 + (-14 - e)", "12 + (-14 - e)", [DTYPES]),
+    ("binary16 narrowing overflows one binade late", "if (e > 15) return", "if (e > 16) return", [DTYPES]),
+    ("binary16 narrowing flushes the smallest subnormal's upper half to zero", "e < -25", "e < -24", [DTYPES]),
     ("typed reduction reads binary16 as bf16",
      "if (dtype == ORC_DTYPE_F16) return orc_f16_widen(((const uint16_t*)buf)[x]);", "", [DTYPES]),
 ]
