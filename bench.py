@@ -55,9 +55,10 @@ def parse_args():
     ap.add_argument("--grad-dtype", choices=["bf16", "f16", "f32"], default="bf16",
                     help="storage format of the gradient buffers the reduce-scatter-accumulate reads "
                          "(rank view, flat layout)")
-    ap.add_argument("--param-dtype", choices=["bf16", "f32"], default="bf16",
+    ap.add_argument("--param-dtype", choices=["bf16", "f16", "f32"], default="bf16",
                     help="f32: plain float32 training -- the gathered parameter has 4-byte elements and "
-                         "the Adam step writes no bf16 copy")
+                         "the Adam step writes no 16-bit copy; f16: the Adam step writes IEEE binary16 "
+                         "parameters (mixed precision without bf16), the gather moves the same 2-byte elements")
     ap.add_argument("--gathers-per-microstep", type=int, default=0,
                     help="run this many extra gather reorders before every reduce-scatter-accumulate, as "
                          "a training run does (parameters are gathered in the forward and in the backward "
@@ -288,14 +289,23 @@ class Workload:
         if a.fused:
             if timed:
                 marks[3].record(stream)
-            m.mics_replica_average_adam_shard(self.master, self.exp_avg, self.exp_avg_sq, self.param, self.copies,
-                                              count, self.scale, step=it, stream=sh, **self.hp)
+            if a.param_dtype == "f16":
+                m.mics_replica_average_adam_shard_typed(self.master, self.exp_avg, self.exp_avg_sq, self.param,
+                                                        m.MICS_DTYPE_F16, self.copies, count, self.scale, step=it,
+                                                        stream=sh, **self.hp)
+            else:
+                m.mics_replica_average_adam_shard(self.master, self.exp_avg, self.exp_avg_sq, self.param,
+                                                  self.copies, count, self.scale, step=it, stream=sh, **self.hp)
         else:
             m.mics_replica_average(self.avg, self.copies, count, self.scale, stream=sh)
             if timed:
                 marks[3].record(stream)
-            m.mics_adam_shard(self.master, self.exp_avg, self.exp_avg_sq, self.param, self.avg, count, step=it,
-                              stream=sh, **self.hp)
+            if a.param_dtype == "f16":
+                m.mics_adam_shard_typed(self.master, self.exp_avg, self.exp_avg_sq, self.param, m.MICS_DTYPE_F16,
+                                        self.avg, count, step=it, stream=sh, **self.hp)
+            else:
+                m.mics_adam_shard(self.master, self.exp_avg, self.exp_avg_sq, self.param, self.avg, count, step=it,
+                                  stream=sh, **self.hp)
         if timed:
             marks[4].record(stream)
             self.marks.append(marks)
@@ -385,7 +395,8 @@ class Workload:
             "higher_is_better": True,
             "scaling": "weak",
             "vs_baseline": None,
-            "dtype": f"{a.grad_dtype} in / f32 accumulate" + (", f32 parameters" if self.pf32 else ""),
+            "dtype": f"{a.grad_dtype} in / f32 accumulate"
+                     + (", f32 parameters" if self.pf32 else ", f16 parameters" if a.param_dtype == "f16" else ""),
             "data": "synthetic",
             "pct_of_peak_hbm": round(100.0 * gbps / PEAK_HBM_GBPS, 2),
             "ms_per_step_events": {key: round(val, 4) for key, val in st_step.items()},

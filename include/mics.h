@@ -199,6 +199,27 @@ int mics_replica_average_adam_shard(float* master, float* exp_avg, float* exp_av
                                     void* stream);
 
 /*
+ * mics_adam_shard and mics_replica_average_adam_shard with the 16-bit parameter copy in a
+ * chosen format.  The paper trains in "mixed-precision" on V100 GPUs, which have no bf16
+ * (Section 5): there the low-precision parameters that the next gather moves are IEEE
+ * binary16.  param_dtype = MICS_DTYPE_BF16 (as in the calls above) or MICS_DTYPE_F16:
+ * param_out[x] = the new master[x] rounded to nearest even in that format (binary16:
+ * subnormals kept, magnitudes of 65520 and above become Inf, NaN stays NaN).
+ * MICS_DTYPE_F32 is MICS_ERR_UNSUPPORTED: the master is the binary32 parameter, pass
+ * param_out = NULL.  param_out: device, count 2-byte elements, written, may be NULL;
+ * everything else as in the calls above, and the fp32 results are the same bit for bit.
+ */
+int mics_adam_shard_typed(float* master, float* exp_avg, float* exp_avg_sq, void* param_out,
+                          int param_dtype, const float* grad, size_t count, float lr,
+                          float beta1, float beta2, float eps, float weight_decay, int step,
+                          void* stream);
+int mics_replica_average_adam_shard_typed(float* master, float* exp_avg, float* exp_avg_sq,
+                                          void* param_out, int param_dtype,
+                                          const float* const* acc_copies, size_t count, int r,
+                                          float scale, float lr, float beta1, float beta2,
+                                          float eps, float weight_decay, int step, void* stream);
+
+/*
  * One separately sharded tensor of a coalesced call.  The paper's coalesced collectives
  * (Section 4, "Coalesced communication APIs": all_gather_coalesced, reduce_scatter_coalesced)
  * launch the per-tensor operations of many tensors at once, with no staging copy; the two

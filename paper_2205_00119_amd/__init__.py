@@ -27,6 +27,7 @@ EXPORTS = (
     "mics_hier_gather_reorder", "mics_reduce_scatter_accum", "mics_replica_average",
     "mics_adam_shard", "mics_hier_gather_reorder_coalesced", "mics_reduce_scatter_accum_coalesced",
     "mics_replica_average_adam_shard", "mics_reduce_scatter_accum_typed",
+    "mics_adam_shard_typed", "mics_replica_average_adam_shard_typed",
 )
 MICS_DTYPE_BF16, MICS_DTYPE_F16, MICS_DTYPE_F32 = 0, 1, 2
 
@@ -91,6 +92,11 @@ lib.mics_replica_average_adam_shard.argtypes = [_vp, _vp, _vp, _vp, _vp, _sz, _i
 lib.mics_replica_average_adam_shard.restype = _i
 
 
+lib.mics_adam_shard_typed.argtypes = [_vp, _vp, _vp, _vp, _i, _vp, _sz, _f, _f, _f, _f, _f, _i, _vp]
+lib.mics_adam_shard_typed.restype = _i
+lib.mics_replica_average_adam_shard_typed.argtypes = [_vp, _vp, _vp, _vp, _i, _vp, _sz, _i, _f, _f, _f, _f, _f,
+                                                      _f, _i, _vp]
+lib.mics_replica_average_adam_shard_typed.restype = _i
 lib.mics_reduce_scatter_accum_typed.argtypes = [_vp, _vp, _sz, _sz, _i, _i, _i, _vp]
 lib.mics_reduce_scatter_accum_typed.restype = _i
 
@@ -214,6 +220,26 @@ def mics_replica_average_adam_shard(master, exp_avg, exp_avg_sq, param_bf16, acc
     """Replica average and Adam step in one pass; same results as the two separate calls."""
     _check(lib.mics_replica_average_adam_shard(
         _dev_ptr(master), _dev_ptr(exp_avg), _dev_ptr(exp_avg_sq), _dev_ptr(param_bf16),
+        _table(acc_copies), count, len(acc_copies), scale, lr, beta1, beta2, eps, weight_decay, step,
+        _stream(stream)))
+
+
+def mics_adam_shard_typed(master, exp_avg, exp_avg_sq, param_out, param_dtype: int, grad, count: int, *,
+                          lr: float, beta1: float, beta2: float, eps: float, weight_decay: float, step: int,
+                          stream=None) -> None:
+    """mics_adam_shard writing the 16-bit parameter as bf16 or binary16 (MICS_DTYPE_*)."""
+    _check(lib.mics_adam_shard_typed(_dev_ptr(master), _dev_ptr(exp_avg), _dev_ptr(exp_avg_sq),
+                                     _dev_ptr(param_out), param_dtype, _dev_ptr(grad), count, lr, beta1, beta2,
+                                     eps, weight_decay, step, _stream(stream)))
+
+
+def mics_replica_average_adam_shard_typed(master, exp_avg, exp_avg_sq, param_out, param_dtype: int,
+                                          acc_copies: Sequence, count: int, scale: float, *, lr: float,
+                                          beta1: float, beta2: float, eps: float, weight_decay: float,
+                                          step: int, stream=None) -> None:
+    """mics_replica_average_adam_shard writing the 16-bit parameter as bf16 or binary16."""
+    _check(lib.mics_replica_average_adam_shard_typed(
+        _dev_ptr(master), _dev_ptr(exp_avg), _dev_ptr(exp_avg_sq), _dev_ptr(param_out), param_dtype,
         _table(acc_copies), count, len(acc_copies), scale, lr, beta1, beta2, eps, weight_decay, step,
         _stream(stream)))
 

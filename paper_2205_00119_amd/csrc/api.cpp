@@ -81,7 +81,7 @@ mics::AdamScalars adam_scalars(float lr, float beta1, float beta2, float eps, fl
 
 extern "C" {
 
-int mics_version(void) { return 200; }
+int mics_version(void) { return 210; }
 
 const char* mics_last_error(void) { return g_error; }
 
@@ -252,12 +252,15 @@ int mics_replica_average(float* out, const float* const* acc_copies,
     return err ? hip_fail(fn, err) : MICS_OK;
 }
 
-int mics_adam_shard(float* master, float* exp_avg, float* exp_avg_sq,
-                    uint16_t* param_bf16, const float* grad, size_t count,
-                    float lr, float beta1, float beta2, float eps,
-                    float weight_decay, int step, void* stream)
+}  // extern "C"
+
+namespace {
+
+// `pname` = what the entry point calls its 16-bit parameter output; f16 = binary16, else bf16.
+int adam_shard(const char* fn, const char* pname, float* master, float* exp_avg, float* exp_avg_sq,
+               uint16_t* param_bf16, bool f16, const float* grad, size_t count, float lr, float beta1,
+               float beta2, float eps, float weight_decay, int step, void* stream)
 {
-    const char* fn = "mics_adam_shard";
     if (step < 1) return fail(MICS_ERR_INVALID_ARG, "%s: step = %d, must be >= 1", fn, step);
     if (!(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f))
         return fail(MICS_ERR_INVALID_ARG, "%s: beta1 = %g, beta2 = %g must lie in [0, 1)", fn,
@@ -276,14 +279,51 @@ int mics_adam_shard(float* master, float* exp_avg, float* exp_avg_sq,
             if (overlaps(f32[a], count * 4, f32[b], count * 4))
                 return fail(MICS_ERR_INVALID_ARG, "%s: %s overlaps %s", fn, name[a], name[b]);
         if (param_bf16 && overlaps(f32[a], count * 4, param_bf16, count * 2))
-            return fail(MICS_ERR_INVALID_ARG, "%s: param_bf16 overlaps %s", fn, name[a]);
+            return fail(MICS_ERR_INVALID_ARG, "%s: %s overlaps %s", fn, pname, name[a]);
     }
     if (param_bf16 && !aligned(param_bf16, 2))
-        return fail(MICS_ERR_ALIGNMENT, "%s: param_bf16 not aligned to 2 bytes", fn);
+        return fail(MICS_ERR_ALIGNMENT, "%s: %s not aligned to 2 bytes", fn, pname);
 
     const mics::AdamScalars hp = adam_scalars(lr, beta1, beta2, eps, weight_decay, step);
-    int err = mics::launch_adam(master, exp_avg, exp_avg_sq, param_bf16, grad, count, hp, stream);
+    int err = mics::launch_adam(master, exp_avg, exp_avg_sq, param_bf16, f16, grad, count, hp, stream);
     return err ? hip_fail(fn, err) : MICS_OK;
+}
+
+// The 16-bit parameter formats of the typed Adam entry points.
+int param_format(const char* fn, int param_dtype, bool* f16)
+{
+    if (param_dtype == MICS_DTYPE_F32)
+        return fail(MICS_ERR_UNSUPPORTED, "%s: param_dtype = MICS_DTYPE_F32: the master is the binary32 parameter; "
+                    "pass param_out = NULL", fn);
+    if (param_dtype != MICS_DTYPE_BF16 && param_dtype != MICS_DTYPE_F16)
+        return fail(MICS_ERR_INVALID_ARG, "%s: param_dtype = %d is not MICS_DTYPE_BF16 or MICS_DTYPE_F16", fn,
+                    param_dtype);
+    *f16 = param_dtype == MICS_DTYPE_F16;
+    return MICS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mics_adam_shard(float* master, float* exp_avg, float* exp_avg_sq,
+                    uint16_t* param_bf16, const float* grad, size_t count,
+                    float lr, float beta1, float beta2, float eps,
+                    float weight_decay, int step, void* stream)
+{
+    return adam_shard("mics_adam_shard", "param_bf16", master, exp_avg, exp_avg_sq, param_bf16, false, grad, count,
+                      lr, beta1, beta2, eps, weight_decay, step, stream);
+}
+
+int mics_adam_shard_typed(float* master, float* exp_avg, float* exp_avg_sq, void* param_out,
+                          int param_dtype, const float* grad, size_t count, float lr, float beta1,
+                          float beta2, float eps, float weight_decay, int step, void* stream)
+{
+    const char* fn = "mics_adam_shard_typed";
+    bool f16 = false;
+    if (int rc = param_format(fn, param_dtype, &f16)) return rc;
+    return adam_shard(fn, "param_out", master, exp_avg, exp_avg_sq, (uint16_t*)param_out, f16, grad, count, lr,
+                      beta1, beta2, eps, weight_decay, step, stream);
 }
 
 int mics_hier_gather_reorder_coalesced(void* dst_flat, const void* const* stage1_bufs,
@@ -436,13 +476,15 @@ int mics_reduce_scatter_accum_coalesced(float* acc, const uint16_t* const* grads
     return MICS_OK;
 }
 
-int mics_replica_average_adam_shard(float* master, float* exp_avg, float* exp_avg_sq,
-                                    uint16_t* param_bf16, const float* const* acc_copies,
-                                    size_t count, int r, float scale, float lr, float beta1,
-                                    float beta2, float eps, float weight_decay, int step,
-                                    void* stream)
+}  // extern "C"
+
+namespace {
+
+int replica_average_adam_shard(const char* fn, const char* pname, float* master, float* exp_avg,
+                               float* exp_avg_sq, uint16_t* param_bf16, bool f16,
+                               const float* const* acc_copies, size_t count, int r, float scale, float lr,
+                               float beta1, float beta2, float eps, float weight_decay, int step, void* stream)
 {
-    const char* fn = "mics_replica_average_adam_shard";
     if (step < 1) return fail(MICS_ERR_INVALID_ARG, "%s: step = %d, must be >= 1", fn, step);
     if (!(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f))
         return fail(MICS_ERR_INVALID_ARG, "%s: beta1 = %g, beta2 = %g must lie in [0, 1)", fn,
@@ -463,10 +505,10 @@ int mics_replica_average_adam_shard(float* master, float* exp_avg, float* exp_av
             if (overlaps(st[a], count * 4, st[b], count * 4))
                 return fail(MICS_ERR_INVALID_ARG, "%s: %s overlaps %s", fn, name[a], name[b]);
         if (param_bf16 && overlaps(st[a], count * 4, param_bf16, count * 2))
-            return fail(MICS_ERR_INVALID_ARG, "%s: param_bf16 overlaps %s", fn, name[a]);
+            return fail(MICS_ERR_INVALID_ARG, "%s: %s overlaps %s", fn, pname, name[a]);
     }
     if (param_bf16 && !aligned(param_bf16, 2))
-        return fail(MICS_ERR_ALIGNMENT, "%s: param_bf16 not aligned to 2 bytes", fn);
+        return fail(MICS_ERR_ALIGNMENT, "%s: %s not aligned to 2 bytes", fn, pname);
     mics::PtrTable tab{};
     for (int c = 0; c < r; ++c) {
         const float* a = acc_copies[c];
@@ -477,13 +519,42 @@ int mics_replica_average_adam_shard(float* master, float* exp_avg, float* exp_av
             if (overlaps(st[b], count * 4, a, count * 4))
                 return fail(MICS_ERR_INVALID_ARG, "%s: %s overlaps acc_copies[%d]", fn, name[b], c);
         if (param_bf16 && overlaps(param_bf16, count * 2, a, count * 4))
-            return fail(MICS_ERR_INVALID_ARG, "%s: param_bf16 overlaps acc_copies[%d]", fn, c);
+            return fail(MICS_ERR_INVALID_ARG, "%s: %s overlaps acc_copies[%d]", fn, pname, c);
         tab.ptr[c] = a;
     }
     const mics::AdamScalars hp = adam_scalars(lr, beta1, beta2, eps, weight_decay, step);
-    int err = mics::launch_avg_adam(master, exp_avg, exp_avg_sq, param_bf16, tab, r, scale, count, hp,
+    int err = mics::launch_avg_adam(master, exp_avg, exp_avg_sq, param_bf16, f16, tab, r, scale, count, hp,
                                     stream);
     return err ? hip_fail(fn, err) : MICS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mics_replica_average_adam_shard(float* master, float* exp_avg, float* exp_avg_sq,
+                                    uint16_t* param_bf16, const float* const* acc_copies,
+                                    size_t count, int r, float scale, float lr, float beta1,
+                                    float beta2, float eps, float weight_decay, int step,
+                                    void* stream)
+{
+    return replica_average_adam_shard("mics_replica_average_adam_shard", "param_bf16", master, exp_avg, exp_avg_sq,
+                                      param_bf16, false, acc_copies, count, r, scale, lr, beta1, beta2, eps,
+                                      weight_decay, step, stream);
+}
+
+int mics_replica_average_adam_shard_typed(float* master, float* exp_avg, float* exp_avg_sq,
+                                          void* param_out, int param_dtype,
+                                          const float* const* acc_copies, size_t count, int r,
+                                          float scale, float lr, float beta1, float beta2, float eps,
+                                          float weight_decay, int step, void* stream)
+{
+    const char* fn = "mics_replica_average_adam_shard_typed";
+    bool f16 = false;
+    if (int rc = param_format(fn, param_dtype, &f16)) return rc;
+    return replica_average_adam_shard(fn, "param_out", master, exp_avg, exp_avg_sq, (uint16_t*)param_out, f16,
+                                      acc_copies, count, r, scale, lr, beta1, beta2, eps, weight_decay, step,
+                                      stream);
 }
 
 }  // extern "C"

@@ -39,12 +39,13 @@ struct AdamScalars {
     float bias_corr1, bias_corr2;  // 1 - beta^step, double on the host, rounded
 };
 
+// param_bf16: the 16-bit copy of the new master (NULL = none), bf16 or, with param_f16, binary16.
 int launch_adam(float* master, float* exp_avg, float* exp_avg_sq,
-                uint16_t* param_bf16, const float* grad, size_t count,
+                uint16_t* param_bf16, bool param_f16, const float* grad, size_t count,
                 const AdamScalars& hp, void* stream);
 
 // Replica average and Adam in one pass (the averaged gradient stays in registers).
-int launch_avg_adam(float* master, float* exp_avg, float* exp_avg_sq, uint16_t* param_bf16,
+int launch_avg_adam(float* master, float* exp_avg, float* exp_avg_sq, uint16_t* param_bf16, bool param_f16,
                     const PtrTable& copies, int r, float scale, size_t count, const AdamScalars& hp,
                     void* stream);
 

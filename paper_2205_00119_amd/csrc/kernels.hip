@@ -226,6 +226,29 @@ __device__ __forceinline__ uint16_t bf16_single(float a)
     return __builtin_bit_cast(uint16_t, h);
 }
 
+// fp32 -> IEEE binary16, round to nearest even, subnormals kept, overflow to Inf.
+__device__ __forceinline__ uint16_t f16_single(float a)
+{
+    _Float16 h = (_Float16)a;
+    return __builtin_bit_cast(uint16_t, h);
+}
+
+// Low-precision copy of the parameters that the Adam kernels write next to the fp32 master.
+enum { kParamNone = 0, kParamBf16 = 1, kParamF16 = 2 };
+
+template <int OUT>
+__device__ __forceinline__ uint32_t param_pack(float a, float b)
+{
+    if constexpr (OUT == kParamBf16) return bf16_pack(a, b);
+    else return (uint32_t)f16_single(a) | ((uint32_t)f16_single(b) << 16);
+}
+template <int OUT>
+__device__ __forceinline__ uint16_t param_single(float a)
+{
+    if constexpr (OUT == kParamBf16) return bf16_single(a);
+    else return f16_single(a);
+}
+
 // ---------------------------------------------------------------------------
 // Step 1: chunk rearrangement of the hierarchical all-gather (Section 3.3).
 // Chunk g of the result comes from slot g div k of the stage-1 buffer of local
@@ -828,7 +851,7 @@ __device__ __forceinline__ void adam_element(float& w, float& m, float& v, float
 }
 
 // The update of 4 consecutive elements from x given their gradient, states in place.
-template <bool BF16>
+template <int OUT>
 __device__ __forceinline__ void adam_update4(float* master, float* exp_avg, float* exp_avg_sq,
                                              uint16_t* param_bf16, size_t x, f32x4 g, f32x4 w, f32x4 m,
                                              f32x4 v, const AdamScalars& hp)
@@ -842,29 +865,29 @@ __device__ __forceinline__ void adam_update4(float* master, float* exp_avg, floa
     MICS_ST(kAdamNts, (f32x4_a4*)(master + x), w);
     MICS_ST(kAdamNts, (f32x4_a4*)(exp_avg + x), m);
     MICS_ST(kAdamNts, (f32x4_a4*)(exp_avg_sq + x), v);
-    if (BF16) {
-        u32x2 b = {bf16_pack(w.x, w.y), bf16_pack(w.z, w.w)};
+    if constexpr (OUT != kParamNone) {
+        u32x2 b = {param_pack<OUT>(w.x, w.y), param_pack<OUT>(w.z, w.w)};
         MICS_ST(kAdamNts, (u32x2_a2*)(param_bf16 + x), b);
     }
 }
 
-template <bool BF16>
+template <int OUT>
 __device__ __forceinline__ void adam_update1(float* master, float* exp_avg, float* exp_avg_sq,
                                              uint16_t* param_bf16, size_t x, float g, const AdamScalars& hp)
 {
     float w = master[x], m = exp_avg[x], v = exp_avg_sq[x];
     adam_element(w, m, v, g, hp);
     master[x] = w; exp_avg[x] = m; exp_avg_sq[x] = v;
-    if (BF16) param_bf16[x] = bf16_single(w);
+    if constexpr (OUT != kParamNone) param_bf16[x] = param_single<OUT>(w);
 }
 
 // One lane owns 4 consecutive elements per pass, so that every load and store instruction of
 // a wavefront covers one contiguous kilobyte (stores that leave gaps between lanes reach
 // memory as partial lines and cost extra traffic).  Four 128-bit loads are in flight before
-// the first use; the bf16 parameters leave as one 64-bit store.  The bf16 output may sit
-// anywhere on an element boundary -- for instance inside the stage-1 buffer of the next
-// parameter gather, at T_l + j*S.
-template <bool BF16>
+// the first use; the 16-bit parameters (bf16 or binary16, OUT) leave as one 64-bit store.  That
+// output may sit anywhere on an element boundary -- for instance inside the stage-1 buffer of
+// the next parameter gather, at T_l + j*S.
+template <int OUT>
 __global__ __launch_bounds__(kMaxBlock) void adam_kernel(
     float* __restrict__ master, float* __restrict__ exp_avg, float* __restrict__ exp_avg_sq,
     uint16_t* __restrict__ param_bf16, const float* __restrict__ grad, size_t count, AdamScalars hp)
@@ -878,10 +901,10 @@ __global__ __launch_bounds__(kMaxBlock) void adam_kernel(
             const f32x4 w = MICS_LD(kAdamNtl, (const f32x4_a4*)(master + x));
             const f32x4 m = MICS_LD(kAdamNtl, (const f32x4_a4*)(exp_avg + x));
             const f32x4 v = MICS_LD(kAdamNtl, (const f32x4_a4*)(exp_avg_sq + x));
-            adam_update4<BF16>(master, exp_avg, exp_avg_sq, param_bf16, x, g, w, m, v, hp);
+            adam_update4<OUT>(master, exp_avg, exp_avg_sq, param_bf16, x, g, w, m, v, hp);
         } else {
             for (size_t e = x; e < count; ++e)
-                adam_update1<BF16>(master, exp_avg, exp_avg_sq, param_bf16, e, grad[e], hp);
+                adam_update1<OUT>(master, exp_avg, exp_avg_sq, param_bf16, e, grad[e], hp);
         }
     }
 }
@@ -891,7 +914,7 @@ __global__ __launch_bounds__(kMaxBlock) void adam_kernel(
 // as avg_kernel) and goes straight into adam_element, so it is neither written nor re-read:
 // 4r + 12 bytes read and 14 written per element instead of (4r + 4) + 30.  R > 0: r = R at
 // compile time; R == 0: any r in batches of 16 loads.
-template <int R, bool BF16, typename Tab>
+template <int R, int OUT, typename Tab>
 __global__ __launch_bounds__(kMaxBlock) void avg_adam_kernel(
     float* __restrict__ master, float* __restrict__ exp_avg, float* __restrict__ exp_avg_sq,
     uint16_t* __restrict__ param_bf16, Tab a, int r, float scale, size_t count, AdamScalars hp)
@@ -910,13 +933,13 @@ __global__ __launch_bounds__(kMaxBlock) void avg_adam_kernel(
 #if !MICS_FUSED_COPIES_FIRST
             const f32x4 sum = avg_sum4<R, MICS_FUSED_NTL_COPIES>(a, r, x);
 #endif
-            adam_update4<BF16>(master, exp_avg, exp_avg_sq, param_bf16, x, sum * scale, w, m, v, hp);
+            adam_update4<OUT>(master, exp_avg, exp_avg_sq, param_bf16, x, sum * scale, w, m, v, hp);
         }
     }
     // the last count mod 4 elements: one per lane
     const size_t e = count / 4 * 4 + threadIdx.x;
     if (blockIdx.x == 0 && e < count)
-        adam_update1<BF16>(master, exp_avg, exp_avg_sq, param_bf16, e, avg_sum1(a, r, e) * scale, hp);
+        adam_update1<OUT>(master, exp_avg, exp_avg_sq, param_bf16, e, avg_sum1(a, r, e) * scale, hp);
 }
 
 // ---------------------------------------------------------------------------
@@ -1237,18 +1260,28 @@ int launch_replica_average(float* out, const PtrTable& a, size_t count, int r, f
     });
 }
 
-int launch_adam(float* master, float* exp_avg, float* exp_avg_sq, uint16_t* param_bf16,
+namespace {
+// Calls f(std::integral_constant<int, OUT>) for the parameter output of a call.
+template <typename F>
+int dispatch_param(const void* param_out, bool f16, F&& f)
+{
+    if (!param_out) return f(std::integral_constant<int, kParamNone>{});
+    if (f16) return f(std::integral_constant<int, kParamF16>{});
+    return f(std::integral_constant<int, kParamBf16>{});
+}
+}  // namespace
+
+int launch_adam(float* master, float* exp_avg, float* exp_avg_sq, uint16_t* param_bf16, bool param_f16,
                 const float* grad, size_t count, const AdamScalars& hp, void* stream)
 {
     hipStream_t st = (hipStream_t)stream;
     unsigned blocks = 0;
     const Shape sh = shape_of(kFamAdam, stream_acc(count), count * 30);
     if (int e = grid_for((count + 3) / 4, sh.lanes, MICS_ADAM_BPC, &blocks)) return e;
-    if (param_bf16)
-        return launch(adam_kernel<true>, dim3(blocks), dim3(sh.lanes), lds_for(sh), st, master, exp_avg, exp_avg_sq,
-                      param_bf16, grad, count, hp);
-    return launch(adam_kernel<false>, dim3(blocks), dim3(sh.lanes), lds_for(sh), st, master, exp_avg, exp_avg_sq,
-                  param_bf16, grad, count, hp);
+    return dispatch_param(param_bf16, param_f16, [&](auto OUT) {
+        return launch(adam_kernel<OUT.value>, dim3(blocks), dim3(sh.lanes), lds_for(sh), st, master, exp_avg,
+                      exp_avg_sq, param_bf16, grad, count, hp);
+    });
 }
 
 int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs, int n, int p, int k,
@@ -1384,7 +1417,7 @@ int launch_reduce_coalesced(float* acc, const PtrTable& grads, const Segment* se
     return 0;
 }
 
-int launch_avg_adam(float* master, float* exp_avg, float* exp_avg_sq, uint16_t* param_bf16,
+int launch_avg_adam(float* master, float* exp_avg, float* exp_avg_sq, uint16_t* param_bf16, bool param_f16,
                     const PtrTable& copies, int r, float scale, size_t count, const AdamScalars& hp,
                     void* stream)
 {
@@ -1393,7 +1426,7 @@ int launch_avg_adam(float* master, float* exp_avg, float* exp_avg_sq, uint16_t* 
     const Shape sh = shape_of(kFamFused, stream_acc(count), count * (4 * (size_t)r + 26), r + 3, 11);
     const size_t lds = lds_for(sh);
     if (int e = grid_for((count + 3) / 4, sh.lanes, MICS_ADAM_BPC, &blocks)) return e;
-    return dispatch2(param_bf16 != nullptr, false, [&](auto BF, auto) {
+    return dispatch_param(param_bf16, param_f16, [&](auto BF) {
         const dim3 gr(blocks), bl(sh.lanes);
         switch (r) {
             case 1: return launch(avg_adam_kernel<1, BF.value, SmallTable<1>>, gr, bl, lds, st, master, exp_avg, exp_avg_sq, param_bf16, small<1>(copies), r, scale, count, hp);

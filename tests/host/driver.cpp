@@ -36,6 +36,16 @@ int main()
                                           (const float* const*)tab.data(), 777, 128, 0.25f, 1e-4f, 0.9f, 0.999f,
                                           1e-8f, 0.0f, 1, nullptr) == MICS_OK);
     CHECK(mics::g_launches == before + 9);
+    before = mics::g_launches;
+    CHECK(mics_adam_shard_typed((float*)fake(1), (float*)fake(2), (float*)fake(3), fake(4), MICS_DTYPE_F16,
+                                (const float*)fake(5), 777, 1e-4f, 0.9f, 0.999f, 1e-8f, 0.01f, 3, nullptr) == MICS_OK);
+    CHECK(mics_replica_average_adam_shard_typed((float*)fake(1), (float*)fake(2), (float*)fake(3), fake(4),
+                                                MICS_DTYPE_F16, (const float* const*)tab.data(), 777, 128, 0.25f,
+                                                1e-4f, 0.9f, 0.999f, 1e-8f, 0.0f, 1, nullptr) == MICS_OK);
+    CHECK(mics_adam_shard_typed((float*)fake(1), (float*)fake(2), (float*)fake(3), fake(4), MICS_DTYPE_F32,
+                                (const float*)fake(5), 777, 1e-4f, 0.9f, 0.999f, 1e-8f, 0.01f, 3, nullptr)
+          == MICS_ERR_UNSUPPORTED);
+    CHECK(mics::g_launches == before + 2);
     // misaligned buffers and odd counts still cost one launch
     before = mics::g_launches;
     for (int i = 0; i < 16; ++i) tab[i] = (const char*)fake(i + 8) + 2 * (i % 2) + 6;

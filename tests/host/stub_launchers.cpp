@@ -8,8 +8,8 @@ int g_launches = 0;
 int launch_reorder(void*, const PtrTable&, size_t, size_t, int, int, bool, void*) { ++g_launches; return 0; }
 int launch_reduce_scatter_accum(float*, const PtrTable&, size_t, int, bool, int, void*) { ++g_launches; return 0; }
 int launch_replica_average(float*, const PtrTable&, size_t, int, float, void*) { ++g_launches; return 0; }
-int launch_adam(float*, float*, float*, uint16_t*, const float*, size_t, const AdamScalars&, void*) { ++g_launches; return 0; }
-int launch_avg_adam(float*, float*, float*, uint16_t*, const PtrTable&, int, float, size_t, const AdamScalars&, void*) { ++g_launches; return 0; }
+int launch_adam(float*, float*, float*, uint16_t*, bool, const float*, size_t, const AdamScalars&, void*) { ++g_launches; return 0; }
+int launch_avg_adam(float*, float*, float*, uint16_t*, bool, const PtrTable&, int, float, size_t, const AdamScalars&, void*) { ++g_launches; return 0; }
 // the real launchers issue one kernel launch per kMaxSegPerLaunch segments
 int launch_reorder_coalesced(void*, const PtrTable&, const Segment*, int n, int, int, int, bool, void*)
 {

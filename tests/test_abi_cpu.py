@@ -139,6 +139,30 @@ def test_fused_average_adam_argument_errors():
     f(w, m, v, pb, C, 0, 0.5, step=1, stream=0, **hp)
 
 
+def test_typed_adam_argument_errors():
+    w, m, v, g, po = (A + BUF * i for i in range(5))
+    C = [A + BUF * (5 + i) for i in range(3)]
+    hp = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0)
+    f = mics.mics_adam_shard_typed
+    expect(mics.MICS_ERR_UNSUPPORTED, "mics_adam_shard_typed: param_dtype = MICS_DTYPE_F32", f, w, m, v, po,
+           mics.MICS_DTYPE_F32, g, 8, step=1, stream=0, **hp)
+    expect(mics.MICS_ERR_INVALID_ARG, "param_dtype = 7", f, w, m, v, po, 7, g, 8, step=1, stream=0, **hp)
+    expect(mics.MICS_ERR_ALIGNMENT, "mics_adam_shard_typed: param_out", f, w, m, v, po + 1, mics.MICS_DTYPE_F16, g, 8,
+           step=1, stream=0, **hp)
+    expect(mics.MICS_ERR_INVALID_ARG, "param_out overlaps grad", f, w, m, v, g + 8, mics.MICS_DTYPE_F16, g, 8,
+           step=1, stream=0, **hp)
+    expect(mics.MICS_ERR_INVALID_ARG, "step = 0", f, w, m, v, po, mics.MICS_DTYPE_F16, g, 8, step=0, stream=0, **hp)
+    f(w, m, v, po, mics.MICS_DTYPE_F16, g, 0, step=1, stream=0, **hp)
+    f(w, m, v, None, mics.MICS_DTYPE_BF16, g, 0, step=1, stream=0, **hp)
+    f = mics.mics_replica_average_adam_shard_typed
+    expect(mics.MICS_ERR_UNSUPPORTED, "mics_replica_average_adam_shard_typed: param_dtype", f, w, m, v, po,
+           mics.MICS_DTYPE_F32, C, 8, 0.5, step=1, stream=0, **hp)
+    expect(mics.MICS_ERR_INVALID_ARG, "param_out overlaps acc_copies[1]", f, w, m, v, po, mics.MICS_DTYPE_F16,
+           [C[0], po + 4], 8, 0.5, step=1, stream=0, **hp)
+    expect(mics.MICS_ERR_INVALID_ARG, "r = 0", f, w, m, v, po, mics.MICS_DTYPE_F16, [], 8, 0.5, step=1, stream=0, **hp)
+    f(w, m, v, po, mics.MICS_DTYPE_F16, C, 0, 0.5, step=1, stream=0, **hp)
+
+
 def test_launch_knob_range():
     mics.mics_set_blocks_per_cu(0)
     with pytest.raises(mics.MicsError):

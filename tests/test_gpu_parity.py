@@ -248,6 +248,95 @@ def test_bf16_narrowing_of_arbitrary_masters(orc):
     assert np.array_equal(pb.cpu().numpy().view(np.uint16), orc.bf16_narrow(f))
 
 
+def f16_ulp_distance(a, b):
+    """Distance of two binary16 bit patterns in units in the last place (+0 and -0 coincide)."""
+    def ordered(x):
+        x = x.astype(np.int32)
+        return np.where(x & 0x8000, -(x & 0x7FFF), x & 0x7FFF)
+    return np.abs(ordered(a) - ordered(b))
+
+
+def test_binary16_narrowing_of_arbitrary_masters(orc):
+    # as above for binary16 parameters: every finite binary32 pattern we feed in, with more weight on
+    # the exponents binary16 can hold, its subnormal range, both overflow edges and every kind of tie
+    rng = np.random.default_rng(12)
+    u = rng.integers(0, 1 << 32, size=1 << 20, dtype=np.uint64).astype(np.uint32)
+    dense = (rng.integers(127 - 27, 127 + 18, size=1 << 20, dtype=np.uint64).astype(np.uint32) << 23) \
+        | rng.integers(0, 1 << 23, size=1 << 20, dtype=np.uint64).astype(np.uint32) \
+        | (rng.integers(0, 2, size=1 << 20, dtype=np.uint64).astype(np.uint32) << 31)
+    h = np.arange(0x7C00, dtype=np.uint16)
+    lo = h.view(np.float16).astype(np.float64)
+    hi = np.where(h == 0x7BFF, 65536.0, (h + 1).astype(np.uint16).view(np.float16).astype(np.float64))
+    mid = ((lo + hi) / 2).astype(np.float32)
+    ties = np.concatenate([mid, np.nextafter(mid, np.float32(np.inf)), np.nextafter(mid, np.float32(-np.inf))])
+    special = np.float32([65504.0, 65519.996, 65520.0, 1e10, -65520.0, 2.0 ** -24, 2.0 ** -25, 2.0 ** -26, 1e-45,
+                          0.0, -0.0, 2.0 ** -14, 3.4e38, -3.4e38])
+    f = np.concatenate([u.view(np.float32), dense.view(np.float32), ties, -ties, special])
+    f = f[np.isfinite(f)]
+    n = f.size
+    for fused in (False, True):
+        w = upload(f.copy())
+        z = [upload(np.zeros(n, np.float32)) for _ in range(3)]
+        ph = torch.empty(n, dtype=torch.int16, device="cuda:0")
+        if fused:
+            mics.mics_replica_average_adam_shard_typed(w, z[0], z[1], ph, mics.MICS_DTYPE_F16, [z[2]], n, 1.0, lr=0.0,
+                                                       beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, step=1)
+        else:
+            mics.mics_adam_shard_typed(w, z[0], z[1], ph, mics.MICS_DTYPE_F16, z[2], n, lr=0.0, beta1=0.9,
+                                       beta2=0.999, eps=1e-8, weight_decay=0.0, step=1)
+        torch.cuda.synchronize()
+        assert np.array_equal(w.cpu().numpy().view(np.uint32), f.view(np.uint32))
+        assert np.array_equal(ph.cpu().numpy().view(np.uint16), orc.f16_narrow(f))
+
+
+@pytest.mark.parametrize("count,skew,r", [(4096, 0, 0), (50003, 1, 0), (30001, 0, 2), (20000, 3, 8), (7, 0, 3)])
+def test_adam_writes_binary16_parameters(orc, gen, count, skew, r):
+    """The typed entry points (r = 0: Adam alone, else the fused replica average + Adam over r
+    copies): fp32 results as with bf16 output, parameters = binary16 of the new master."""
+    hp = dict(HP, weight_decay=0.01)
+    w0 = gen.fill_host(gen.stream_key(520, gen.ROLE_MASTER), 0, count, gen.normal_table(0.02, "f32"))
+    w = Guarded(count, np.float32, skew=skew, fill=w0)
+    m = Guarded(count, np.float32, skew=skew, fill=np.zeros(count, np.float32))
+    v = Guarded(count, np.float32, skew=skew, fill=np.zeros(count, np.float32))
+    ph = Guarded(count, np.uint16, skew=skew)
+    pbf = Guarded(count, np.uint16, skew=skew)
+    wr, mr, vr = w0.copy(), np.zeros(count, np.float32), np.zeros(count, np.float32)
+    w64, m64, v64 = w0.copy(), np.zeros(count, np.float32), np.zeros(count, np.float32)
+    scale = 0.125
+    for t in (1, 2):
+        if r:
+            copies = [gen.fill_host(gen.stream_key(521, gen.ROLE_ACC, t, c), 0, count, gen.normal_table(2e-5, "f32"))
+                      for c in range(r)]
+            g_host = orc.replica_average(copies, scale)
+            mics.mics_replica_average_adam_shard_typed(w.t, m.t, v.t, ph.t, mics.MICS_DTYPE_F16,
+                                                       [upload(c) for c in copies], count, scale, step=t, **hp)
+        else:
+            g_host = gen.fill_host(gen.stream_key(521, gen.ROLE_ACC, t), 0, count, gen.normal_table(2.6e-6, "f32"))
+            mics.mics_adam_shard_typed(w.t, m.t, v.t, ph.t, mics.MICS_DTYPE_F16, upload(g_host), count, step=t, **hp)
+        torch.cuda.synchronize()
+        w64[:], m64[:], v64[:] = wr, mr, vr                   # both variants step from the same state
+        p64 = orc.adam_shard(w64, m64, v64, g_host, step=t, param_dtype="f16", **hp)
+        p32 = orc.adam_shard(wr, mr, vr, g_host, step=t, f32=True, param_dtype="f16", **hp)
+        assert np.array_equal(w.numpy().view(np.uint32), wr.view(np.uint32))
+        assert np.array_equal(m.numpy().view(np.uint32), mr.view(np.uint32))
+        assert np.array_equal(v.numpy().view(np.uint32), vr.view(np.uint32))
+        assert np.array_equal(ph.numpy(), p32)
+        assert f16_ulp_distance(ph.numpy(), p64).max() <= 1
+    # the typed call with MICS_DTYPE_BF16 is the plain call
+    w2 = upload(w0.copy())
+    z = [upload(np.zeros(count, np.float32)) for _ in range(2)]
+    w3 = upload(w0.copy())
+    z3 = [upload(np.zeros(count, np.float32)) for _ in range(2)]
+    g = upload(g_host)
+    pb3 = torch.empty(count, dtype=torch.int16, device="cuda:0")
+    mics.mics_adam_shard_typed(w2, z[0], z[1], pbf.t, mics.MICS_DTYPE_BF16, g, count, step=1, **hp)
+    mics.mics_adam_shard(w3, z3[0], z3[1], pb3, g, count, step=1, **hp)
+    torch.cuda.synchronize()
+    assert np.array_equal(pbf.numpy(), pb3.cpu().numpy().view(np.uint16))
+    assert np.array_equal(w2.cpu().numpy().view(np.uint32), w3.cpu().numpy().view(np.uint32))
+    assert all(x.guards_intact() for x in (w, m, v, ph, pbf))
+
+
 def test_adam_handles_denormal_and_huge_inputs_like_the_oracle(orc):
     g = np.array([1e-42, -3e-40, 0.0, 1e-30, 1e15, -1e18, 1e-20, 5e-39] * 16, np.float32)
     n = g.size
