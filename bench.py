@@ -53,8 +53,7 @@ def parse_args():
                          "a configuration of shard alignment 1 every tensor gets 5 extra elements, so "
                          "that no shard, offset or chunk is 16-byte clean")
     ap.add_argument("--grad-dtype", choices=["bf16", "f16", "f32"], default="bf16",
-                    help="storage format of the gradient buffers the reduce-scatter-accumulate reads "
-                         "(rank view, flat layout)")
+                    help="storage format of the gradient buffers the reduce-scatter-accumulate reads")
     ap.add_argument("--param-dtype", choices=["bf16", "f16", "f32"], default="bf16",
                     help="f32: plain float32 training -- the gathered parameter has 4-byte elements and "
                          "the Adam step writes no 16-bit copy; f16: the Adam step writes IEEE binary16 "
@@ -153,6 +152,21 @@ class Workload:
         self.gb = 4 if args.grad_dtype == "f32" else 2
         self.grad_code = {"bf16": mics.MICS_DTYPE_BF16, "f16": mics.MICS_DTYPE_F16,
                           "f32": mics.MICS_DTYPE_F32}[args.grad_dtype]
+
+        def grad_tables_for(fmt):
+            """(torch dtype of a gradient buffer, value table, outlier table) for a storage format."""
+            if fmt == "bf16":
+                return torch.int16, tab_g, tab_go
+            if fmt == "f16":
+                as_f16 = lambda sig: torch.from_numpy(
+                    synth.normal_table(sig, "f32").astype(np.float16).view(np.int16)).to(dev)
+                return (torch.int16, as_f16(cfg.sigma_grad * 1024),                     # loss-scaled by 2^10
+                        as_f16(cfg.sigma_grad * 1024 * cfg.outlier_scale) if cfg.outlier_frac else None)
+            return (torch.float32, torch.from_numpy(synth.normal_table(cfg.sigma_grad, "f32")).to(dev),
+                    torch.from_numpy(synth.normal_table(cfg.sigma_grad * cfg.outlier_scale, "f32")).to(dev)
+                    if cfg.outlier_frac else None)
+
+        g_dt, g_tab, g_out = grad_tables_for(args.grad_dtype)
         if not args.coalesced:
             self.N, self.S = N, S = cfg.N, cfg.S
             n_pad = cfg.N_pad
@@ -174,20 +188,7 @@ class Workload:
             n_sets = 1 if group else s
             lead = offset % 8
             row = -(-(lead + count) // 8) * 8
-            if args.grad_dtype == "bf16":
-                grads = torch.empty((n_sets, p, row), dtype=torch.int16, device=dev)
-                g_tab, g_out = tab_g, tab_go
-            elif args.grad_dtype == "f16":
-                grads = torch.empty((n_sets, p, row), dtype=torch.int16, device=dev)
-                as_f16 = lambda sig: torch.from_numpy(
-                    synth.normal_table(sig, "f32").astype(np.float16).view(np.int16)).to(dev)
-                g_tab = as_f16(cfg.sigma_grad * 1024)          # loss-scaled by 2^10
-                g_out = as_f16(cfg.sigma_grad * 1024 * cfg.outlier_scale) if cfg.outlier_frac else None
-            else:
-                grads = torch.empty((n_sets, p, row), dtype=torch.float32, device=dev)
-                g_tab = torch.from_numpy(synth.normal_table(cfg.sigma_grad, "f32")).to(dev)
-                g_out = (torch.from_numpy(synth.normal_table(cfg.sigma_grad * cfg.outlier_scale, "f32")).to(dev)
-                         if cfg.outlier_frac else None)
+            grads = torch.empty((n_sets, p, row), dtype=g_dt, device=dev)
             for t in range(n_sets):
                 for q in range(p):
                     fill(grads[t, q, lead:lead + count], synth.stream_key(cfg.seed, synth.ROLE_GRAD, 0, t, q),
@@ -197,8 +198,6 @@ class Workload:
         else:
             if group or cfg.name == "tiny":
                 raise SystemExit("--coalesced needs a transformer-layer configuration in rank view")
-            if args.grad_dtype != "bf16":
-                raise SystemExit("--grad-dtype other than bf16 is for the flat layout")
             h = int(cfg.name[1:].split("_")[0])
             numels = [n for _, n in synth.layer_tensors(h)]
             if cfg.align != 8:
@@ -219,12 +218,12 @@ class Workload:
             self.reorder_segs = mics._segments(lay.reorder_segments())
             # a2: every rank's full gradient buffer (all tensors, p*S_t each); the rank reads its slices
             # distinct gradient data per micro-step as far as ~120 GB go (every set is far beyond any cache)
-            n_sets = max(1, min(s, 4, int(120e9 // (2 * p * lay.grad_off[-1]))))
-            grads = torch.empty((n_sets, p, -(-lay.grad_off[-1] // 8) * 8), dtype=torch.int16, device=dev)
+            n_sets = max(1, min(s, 4, int(120e9 // (self.gb * p * lay.grad_off[-1]))))
+            grads = torch.empty((n_sets, p, -(-lay.grad_off[-1] // 8) * 8), dtype=g_dt, device=dev)
             for t in range(n_sets):
                 for q in range(p):
-                    fill(grads[t, q], synth.stream_key(cfg.seed, synth.ROLE_GRAD, 0, t, q), 0, tab_g, 2,
-                         tab_go, cfg.outlier_frac)
+                    fill(grads[t, q], synth.stream_key(cfg.seed, synth.ROLE_GRAD, 0, t, q), 0, g_tab, self.gb,
+                         g_out, cfg.outlier_frac)
             self.grads = grads
             self.grad_tables = [[grads[t % n_sets, q] for q in range(p)] for t in range(s)]
             self.reduce_segs = mics._segments(lay.reduce_segments(args.rank))
@@ -277,7 +276,10 @@ class Workload:
         for t in range(cfg.s):
             for _ in range(a.gathers_per_microstep):
                 self.gather()
-            if a.coalesced:
+            if a.coalesced and a.grad_dtype != "bf16":
+                m.mics_reduce_scatter_accum_coalesced_typed(self.acc, self.grad_tables[t], self.reduce_segs, t > 0,
+                                                            self.grad_code, stream=sh)
+            elif a.coalesced:
                 m.mics_reduce_scatter_accum_coalesced(self.acc, self.grad_tables[t], self.reduce_segs, t > 0, stream=sh)
             elif a.grad_dtype != "bf16":
                 m.mics_reduce_scatter_accum_typed(self.acc, self.grad_tables[t], 0, count, t > 0, self.grad_code,

@@ -260,6 +260,16 @@ int mics_reduce_scatter_accum_coalesced(float* acc, const uint16_t* const* grads
                                         const mics_segment* segs, int n_segs, int p,
                                         int accumulate, void* stream);
 
+/*
+ * mics_reduce_scatter_accum_coalesced for gradient buffers stored as bf16, IEEE binary16 or
+ * binary32 (grad_dtype = MICS_DTYPE_*, as in mics_reduce_scatter_accum_typed): the paper's own
+ * runs put binary16 gradients through its coalesced reduce-scatter (Sections 4 and 5).
+ * grads: host table of p device pointers; offsets and sizes in elements of that format.
+ */
+int mics_reduce_scatter_accum_coalesced_typed(float* acc, const void* const* grads,
+                                              const mics_segment* segs, int n_segs, int p,
+                                              int accumulate, int grad_dtype, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -233,6 +233,16 @@ def reduce_scatter_accum_typed(acc, grads: Sequence[np.ndarray], elem_offset: in
     return acc
 
 
+def reduce_scatter_accum_coalesced_typed(acc, grads: Sequence[np.ndarray], segs, accumulate: bool,
+                                         dtype: int) -> np.ndarray:
+    """reduce_scatter_accum_coalesced for bf16 / binary16 / float32 gradient buffers: the typed
+    reduction, segment by segment."""
+    acc = _c(acc, np.float32)
+    for count, _, src_off, dst_off in segs:
+        reduce_scatter_accum_typed(acc[dst_off:dst_off + count], grads, src_off, accumulate, dtype)
+    return acc
+
+
 def reduce_scatter_accum(acc, grads: Sequence[np.ndarray], elem_offset: int, accumulate: bool,
                          f64: bool = False) -> np.ndarray:
     """In place on ``acc`` (float32, or float64 with ``f64=True``); returns it."""

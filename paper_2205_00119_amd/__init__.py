@@ -28,6 +28,7 @@ EXPORTS = (
     "mics_adam_shard", "mics_hier_gather_reorder_coalesced", "mics_reduce_scatter_accum_coalesced",
     "mics_replica_average_adam_shard", "mics_reduce_scatter_accum_typed",
     "mics_adam_shard_typed", "mics_replica_average_adam_shard_typed",
+    "mics_reduce_scatter_accum_coalesced_typed",
 )
 MICS_DTYPE_BF16, MICS_DTYPE_F16, MICS_DTYPE_F32 = 0, 1, 2
 
@@ -92,6 +93,9 @@ lib.mics_replica_average_adam_shard.argtypes = [_vp, _vp, _vp, _vp, _vp, _sz, _i
 lib.mics_replica_average_adam_shard.restype = _i
 
 
+lib.mics_reduce_scatter_accum_coalesced_typed.argtypes = [_vp, _vp, ctypes.POINTER(mics_segment), _i, _i, _i, _i,
+                                                          _vp]
+lib.mics_reduce_scatter_accum_coalesced_typed.restype = _i
 lib.mics_adam_shard_typed.argtypes = [_vp, _vp, _vp, _vp, _i, _vp, _sz, _f, _f, _f, _f, _f, _i, _vp]
 lib.mics_adam_shard_typed.restype = _i
 lib.mics_replica_average_adam_shard_typed.argtypes = [_vp, _vp, _vp, _vp, _i, _vp, _sz, _i, _f, _f, _f, _f, _f,
@@ -222,6 +226,14 @@ def mics_replica_average_adam_shard(master, exp_avg, exp_avg_sq, param_bf16, acc
         _dev_ptr(master), _dev_ptr(exp_avg), _dev_ptr(exp_avg_sq), _dev_ptr(param_bf16),
         _table(acc_copies), count, len(acc_copies), scale, lr, beta1, beta2, eps, weight_decay, step,
         _stream(stream)))
+
+
+def mics_reduce_scatter_accum_coalesced_typed(acc, grads: Sequence, segs, accumulate: bool, grad_dtype: int,
+                                              stream=None) -> None:
+    """mics_reduce_scatter_accum_coalesced for bf16 / fp16 / fp32 gradient buffers (MICS_DTYPE_*)."""
+    arr = segs if isinstance(segs, ctypes.Array) else _segments(segs)
+    _check(lib.mics_reduce_scatter_accum_coalesced_typed(_dev_ptr(acc), _table(grads), arr, len(arr), len(grads),
+                                                         int(bool(accumulate)), grad_dtype, _stream(stream)))
 
 
 def mics_adam_shard_typed(master, exp_avg, exp_avg_sq, param_out, param_dtype: int, grad, count: int, *,

@@ -413,17 +413,22 @@ int mics_hier_gather_reorder_coalesced(void* dst_flat, const void* const* stage1
     return MICS_OK;
 }
 
-int mics_reduce_scatter_accum_coalesced(float* acc, const uint16_t* const* grads_bf16,
-                                        const mics_segment* segs, int n_segs, int p,
-                                        int accumulate, void* stream)
+}  // extern "C"
+
+namespace {
+
+// `table` = what the entry point calls its pointer table; kind: 0 bf16, 1 binary16, 2 binary32.
+int reduce_scatter_accum_coalesced(const char* fn, const char* table, float* acc, const void* const* grads,
+                                   const mics_segment* segs, int n_segs, int p, int accumulate, int kind,
+                                   void* stream)
 {
-    const char* fn = "mics_reduce_scatter_accum_coalesced";
+    const size_t gb = kind == 2 ? 4 : 2;
     if (p < 1 || p > MICS_MAX_GROUP)
         return fail(MICS_ERR_INVALID_ARG, "%s: p = %d not in [1, %d]", fn, p, MICS_MAX_GROUP);
     if (n_segs < 0) return fail(MICS_ERR_INVALID_ARG, "%s: n_segs = %d is negative", fn, n_segs);
     if (n_segs == 0) return MICS_OK;
     if (!segs) return fail(MICS_ERR_INVALID_ARG, "%s: segs is NULL", fn);
-    if (!grads_bf16) return fail(MICS_ERR_INVALID_ARG, "%s: grads_bf16 is NULL", fn);
+    if (!grads) return fail(MICS_ERR_INVALID_ARG, "%s: %s is NULL", fn, table);
     if (!acc) return fail(MICS_ERR_INVALID_ARG, "%s: acc is NULL", fn);
     if (!aligned(acc, 4)) return fail(MICS_ERR_ALIGNMENT, "%s: acc not aligned to 4 bytes", fn);
     const size_t limit = SIZE_MAX / 16;
@@ -441,12 +446,12 @@ int mics_reduce_scatter_accum_coalesced(float* acc, const uint16_t* const* grads
     }
     mics::PtrTable tab{};
     for (int q = 0; q < p; ++q) {
-        const uint16_t* g = grads_bf16[q];
-        if (!g) return fail(MICS_ERR_INVALID_ARG, "%s: grads_bf16[%d] is NULL", fn, q);
-        if (!aligned(g, 2))
-            return fail(MICS_ERR_ALIGNMENT, "%s: grads_bf16[%d] not aligned to 2 bytes", fn, q);
-        if (total && overlaps(acc + dst_lo, (dst_hi - dst_lo) * 4, g + src_lo, (src_hi - src_lo) * 2))
-            return fail(MICS_ERR_INVALID_ARG, "%s: acc overlaps grads_bf16[%d]", fn, q);
+        const char* g = (const char*)grads[q];
+        if (!g) return fail(MICS_ERR_INVALID_ARG, "%s: %s[%d] is NULL", fn, table, q);
+        if (!aligned(g, gb))
+            return fail(MICS_ERR_ALIGNMENT, "%s: %s[%d] not aligned to %zu bytes", fn, table, q, gb);
+        if (total && overlaps(acc + dst_lo, (dst_hi - dst_lo) * 4, g + src_lo * gb, (src_hi - src_lo) * gb))
+            return fail(MICS_ERR_INVALID_ARG, "%s: acc overlaps %s[%d]", fn, table, q);
         tab.ptr[q] = g;
     }
     if (total == 0) return MICS_OK;
@@ -468,12 +473,34 @@ int mics_reduce_scatter_accum_coalesced(float* acc, const uint16_t* const* grads
             ++nb;
         }
         if (nb == mics::kMaxSegPerLaunch || (last && nb)) {
-            int err = mics::launch_reduce_coalesced(acc, tab, batch, nb, p, accumulate != 0, stream);
+            int err = mics::launch_reduce_coalesced(acc, tab, batch, nb, p, accumulate != 0, kind, stream);
             if (err) return hip_fail(fn, err);
             nb = 0;
         }
     }
     return MICS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mics_reduce_scatter_accum_coalesced(float* acc, const uint16_t* const* grads_bf16,
+                                        const mics_segment* segs, int n_segs, int p,
+                                        int accumulate, void* stream)
+{
+    return reduce_scatter_accum_coalesced("mics_reduce_scatter_accum_coalesced", "grads_bf16", acc,
+                                          (const void* const*)grads_bf16, segs, n_segs, p, accumulate, 0, stream);
+}
+
+int mics_reduce_scatter_accum_coalesced_typed(float* acc, const void* const* grads,
+                                              const mics_segment* segs, int n_segs, int p,
+                                              int accumulate, int grad_dtype, void* stream)
+{
+    const char* fn = "mics_reduce_scatter_accum_coalesced_typed";
+    if (grad_dtype != MICS_DTYPE_BF16 && grad_dtype != MICS_DTYPE_F16 && grad_dtype != MICS_DTYPE_F32)
+        return fail(MICS_ERR_UNSUPPORTED, "%s: grad_dtype = %d is not bf16, f16 or f32", fn, grad_dtype);
+    return reduce_scatter_accum_coalesced(fn, "grads", acc, grads, segs, n_segs, p, accumulate, grad_dtype, stream);
 }
 
 }  // extern "C"

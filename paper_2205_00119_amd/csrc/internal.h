@@ -62,9 +62,9 @@ struct Segment {
 // takes any element-aligned geometry.
 int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs, int n, int p,
                              int k, int elem_bytes, bool vec16, void* stream);
-// numel = elements to reduce; any element-aligned geometry.
+// numel = elements to reduce; any element-aligned geometry.  kind: 0 bf16, 1 binary16, 2 binary32.
 int launch_reduce_coalesced(float* acc, const PtrTable& grads, const Segment* segs, int n, int p,
-                            bool accumulate, void* stream);
+                            bool accumulate, int kind, void* stream);
 
 // Kernel families whose launch shape can be set (mics_tuning.h).
 enum { kFamReorder = 0, kFamReduce = 1, kFamAverage = 2, kFamAdam = 3, kFamFused = 4, kFamilies = 5 };

@@ -721,11 +721,11 @@ __global__ __launch_bounds__(VEC == 4 ? kMaxBlock : kNarrowBlock) void rsa_kerne
         rsa_lane<KIND, VEC, P, BATCH, ACCUM, SA>(acc, g, p, 0, (base + threadIdx.x) * EPL, lead, end);
 }
 
-// Coalesced form (many separately sharded tensors in one launch, bf16): workgroup x works on
+// Coalesced form (many separately sharded tensors in one launch): workgroup x works on
 // tile x - tile_begin[t] of segment t.  Every segment has its own virtual index space as in
-// rsa_kernel: src0 = position of its virtual element 0 in the rank buffers (a multiple of 2
-// elements from the 4-byte aligned base), [lead, end) = its elements, dst = accumulator
-// index of virtual element `lead`.
+// rsa_kernel: src0 = position of its virtual element 0 in the rank buffers (for 2-byte
+// gradients a multiple of 2 elements from the 4-byte aligned base), [lead, end) = its elements,
+// dst = accumulator index of virtual element `lead`.
 struct ReduceSeg {
     unsigned long long end, src0, dst;
     unsigned lead, pad;
@@ -736,16 +736,17 @@ struct ReduceSegTable {
     ReduceSeg seg[kMaxSeg];
 };
 
-template <int P, bool ACCUM, bool SA, typename Tab>
+template <int KIND, int P, bool ACCUM, bool SA, typename Tab>
 __global__ __launch_bounds__(kMaxBlock) void rsa_seg_kernel(
     float* __restrict__ acc, Tab g, int p, ReduceSegTable tab)
 {
+    constexpr int EPL = 4 * GradFormat<KIND>::kPerDword;
     const unsigned x = blockIdx.x;
     const int t = segment_of(tab.tile_begin, x);
     const size_t end = tab.seg[t].end, lead = tab.seg[t].lead;
-    const size_t v0 = ((size_t)(x - tab.tile_begin[t]) * blockDim.x + threadIdx.x) * 8;
-    if (x == tab.tile_begin[t]) rsa_edges<0, 8, ACCUM>(acc + tab.seg[t].dst, g, p, tab.seg[t].src0, lead, end);
-    rsa_lane<0, 4, P, MICS_RSA_BATCH, ACCUM, SA>(acc + tab.seg[t].dst, g, p, tab.seg[t].src0, v0, lead, end);
+    const size_t v0 = ((size_t)(x - tab.tile_begin[t]) * blockDim.x + threadIdx.x) * EPL;
+    if (x == tab.tile_begin[t]) rsa_edges<KIND, EPL, ACCUM>(acc + tab.seg[t].dst, g, p, tab.seg[t].src0, lead, end);
+    rsa_lane<KIND, 4, P, MICS_RSA_BATCH, ACCUM, SA>(acc + tab.seg[t].dst, g, p, tab.seg[t].src0, v0, lead, end);
 }
 
 // ---------------------------------------------------------------------------
@@ -1361,12 +1362,14 @@ int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs
     return 0;
 }
 
-int launch_reduce_coalesced(float* acc, const PtrTable& grads, const Segment* segs, int n, int p,
-                            bool accumulate, void* stream)
+namespace {
+
+template <int KIND>
+int reduce_coalesced_kind(float* acc, PtrTable g, const Segment* segs, int n, int p, bool accumulate,
+                          hipStream_t st)
 {
-    hipStream_t st = (hipStream_t)stream;
-    PtrTable g = grads;
-    const size_t base_lead = align_gradient_pointers(g, p, 2);
+    constexpr size_t GB = GradFormat<KIND>::kElemBytes, EPL = 4 * GradFormat<KIND>::kPerDword;
+    const size_t base_lead = align_gradient_pointers(g, p, (int)GB);
     for (int first = 0; first < n; first += kMaxSeg) {
         ReduceSegTable tab;
         tab.n = n - first < kMaxSeg ? n - first : kMaxSeg;
@@ -1374,21 +1377,22 @@ int launch_reduce_coalesced(float* acc, const PtrTable& grads, const Segment* se
         for (int t = 0; t < tab.n; ++t) elements += segs[first + t].numel;
         const bool streamed = stream_acc(elements, p);
         // as in rsa_launch_kind: single-wavefront workgroups if every access is 16-byte aligned
-        // (h = 8192 layer: 6460 against 6220 GB/s), full-size ones otherwise
-        Shape sh = shape_of(kFamReduce, streamed, elements * (2 * (size_t)p + 8), p + 2, 18);
+        // (h = 8192 layer: 6460 against 6220 GB/s), full-size ones otherwise; binary16 uncapped
+        Shape sh = shape_of(kFamReduce, streamed, elements * (GB * (size_t)p + 8), p + 2, 18);
         bool aligned16 = base_lead == 0 && ((uintptr_t)acc & 15) == 0;
         for (int q = 0; q < p && aligned16; ++q) aligned16 = ((uintptr_t)g.ptr[q] & 15) == 0;
         for (int t = 0; t < tab.n && aligned16; ++t)
-            aligned16 = segs[first + t].src_offset % 8 == 0 && segs[first + t].dst_offset % 4 == 0;
+            aligned16 = segs[first + t].src_offset % (16 / GB) == 0 && segs[first + t].dst_offset % 4 == 0;
         if (!aligned16 && g_lanes[kFamReduce].load() == 0) sh = Shape{MICS_RSA_UNALIGNED_BLOCK, 0};
-        const size_t tile_elems = (size_t)sh.lanes * 8;
+        if (KIND == 1 && g_waves[kFamReduce].load() == 0) sh.waves_per_cu = 0;
+        const size_t tile_elems = (size_t)sh.lanes * EPL;
         size_t tiles = 0;
         for (int t = 0; t < tab.n; ++t) {
             const Segment& sg = segs[first + t];
-            // position of the segment's first element in the rounded-down buffers; its virtual
-            // element 0 is the even position at or below it
+            // position of the segment's first element in the (for 2-byte gradients rounded-down)
+            // buffers; its virtual element 0 is the 4-byte aligned position at or below it
             const size_t src = sg.src_offset + base_lead;
-            const unsigned lead = (unsigned)(src & 1);
+            const unsigned lead = GB == 2 ? (unsigned)(src & 1) : 0u;
             tab.tile_begin[t] = (unsigned)tiles;
             tab.seg[t].lead = lead;
             tab.seg[t].pad = 0;
@@ -1402,19 +1406,42 @@ int launch_reduce_coalesced(float* acc, const PtrTable& grads, const Segment* se
         for (int t = tab.n; t <= kMaxSeg; ++t) tab.tile_begin[t] = 0xFFFFFFFFu;
         if (tiles == 0) continue;
         const int err = dispatch2(accumulate, streamed, [&](auto A, auto SA) {
-            const size_t lds = lds_for(sh, SA.value ? (size_t)sh.lanes * 32 : 0);
-            return dispatch_group(p, [&](auto P) {
-                if constexpr (P.value > 0)
-                    return launch(rsa_seg_kernel<P.value, A.value, SA.value, SmallTable<P.value>>,
-                                  dim3((unsigned)tiles), dim3(sh.lanes), lds, st, acc, small<P.value>(g), p, tab);
-                else
-                    return launch(rsa_seg_kernel<0, A.value, SA.value, PtrTable>, dim3((unsigned)tiles),
-                                  dim3(sh.lanes), lds, st, acc, g, p, tab);
-            });
+            // the streamed-accumulator kernels pass their results through 32 bytes of LDS per lane
+            const size_t lds = lds_for(sh, SA.value && EPL == 8 ? (size_t)sh.lanes * 32 : 0);
+            const dim3 gr((unsigned)tiles), bl(sh.lanes);
+            if constexpr (KIND == 0) {
+                return dispatch_group(p, [&](auto P) {
+                    if constexpr (P.value > 0)
+                        return launch(rsa_seg_kernel<KIND, P.value, A.value, SA.value, SmallTable<P.value>>, gr, bl,
+                                      lds, st, acc, small<P.value>(g), p, tab);
+                    else
+                        return launch(rsa_seg_kernel<KIND, 0, A.value, SA.value, PtrTable>, gr, bl, lds, st, acc, g,
+                                      p, tab);
+                });
+            } else {
+                switch (p) {
+                    case 8: return launch(rsa_seg_kernel<KIND, 8, A.value, SA.value, SmallTable<8>>, gr, bl, lds, st, acc, small<8>(g), p, tab);
+                    case 16: return launch(rsa_seg_kernel<KIND, 16, A.value, SA.value, SmallTable<16>>, gr, bl, lds, st, acc, small<16>(g), p, tab);
+                    default: return launch(rsa_seg_kernel<KIND, 0, A.value, SA.value, PtrTable>, gr, bl, lds, st, acc, g, p, tab);
+                }
+            }
         });
         if (err) return err;
     }
     return 0;
+}
+
+}  // namespace
+
+int launch_reduce_coalesced(float* acc, const PtrTable& grads, const Segment* segs, int n, int p,
+                            bool accumulate, int kind, void* stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    switch (kind) {
+        case 0: return reduce_coalesced_kind<0>(acc, grads, segs, n, p, accumulate, st);
+        case 1: return reduce_coalesced_kind<1>(acc, grads, segs, n, p, accumulate, st);
+        default: return reduce_coalesced_kind<2>(acc, grads, segs, n, p, accumulate, st);
+    }
 }
 
 int launch_avg_adam(float* master, float* exp_avg, float* exp_avg_sq, uint16_t* param_bf16, bool param_f16,

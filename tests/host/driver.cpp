@@ -94,7 +94,8 @@ int main()
         for (auto& sg : layer) { red.push_back({sg.shard_elems, 0, go + 3 * sg.shard_elems, ao}); go += 8 * sg.shard_elems; ao += sg.shard_elems; }
         before = mics::g_launches;
         CHECK(mics_reduce_scatter_accum_coalesced((float*)A, (const uint16_t* const*)tab.data(), red.data(), 16, 8, 0, nullptr) == MICS_OK);
-        CHECK(mics::g_launches == before + 1);
+        CHECK(mics_reduce_scatter_accum_coalesced_typed((float*)A, (const void* const*)tab.data(), red.data(), 16, 8, 1, MICS_DTYPE_F32, nullptr) == MICS_OK);
+        CHECK(mics::g_launches == before + 2);
     }
 
     // rejected calls never reach a launcher

@@ -16,7 +16,7 @@ int launch_reorder_coalesced(void*, const PtrTable&, const Segment*, int n, int,
     g_launches += (n + kMaxSegPerLaunch - 1) / kMaxSegPerLaunch;
     return 0;
 }
-int launch_reduce_coalesced(float*, const PtrTable&, const Segment*, int n, int, bool, void*)
+int launch_reduce_coalesced(float*, const PtrTable&, const Segment*, int n, int, bool, int, void*)
 {
     g_launches += (n + kMaxSegPerLaunch - 1) / kMaxSegPerLaunch;
     return 0;

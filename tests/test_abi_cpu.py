@@ -139,6 +139,22 @@ def test_fused_average_adam_argument_errors():
     f(w, m, v, pb, C, 0, 0.5, step=1, stream=0, **hp)
 
 
+def test_typed_coalesced_reduce_argument_errors():
+    g = mics.mics_reduce_scatter_accum_coalesced_typed
+    G = [A + BUF * (i + 1) for i in range(4)]
+    expect(mics.MICS_ERR_UNSUPPORTED, "grad_dtype = 9", g, A, G, [(8, 0, 0, 0)], False, 9, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "mics_reduce_scatter_accum_coalesced_typed: grads[3] is NULL", g, A,
+           G[:3] + [None], [(8, 0, 0, 0)], False, mics.MICS_DTYPE_F16, stream=0)
+    expect(mics.MICS_ERR_ALIGNMENT, "grads[1] not aligned to 4 bytes", g, A, [G[0], G[1] + 2, G[2]], [(8, 0, 0, 0)],
+           False, mics.MICS_DTYPE_F32, stream=0)
+    g(A, [G[0], G[1] + 2, G[2]], [(0, 0, 0, 0)], False, mics.MICS_DTYPE_F16, stream=0)
+    # binary32 elements are twice as long: the same segment overlaps the accumulator only then
+    expect(mics.MICS_ERR_INVALID_ARG, "acc overlaps grads[0]", g, A + 48, [A, G[1]], [(16, 0, 0, 0)], False,
+           mics.MICS_DTYPE_F32, stream=0)
+    expect(mics.MICS_ERR_INVALID_ARG, "overlap", g, A, G, [(8, 0, 0, 0), (8, 0, 64, 4)], False,
+           mics.MICS_DTYPE_F16, stream=0)
+
+
 def test_typed_adam_argument_errors():
     w, m, v, g, po = (A + BUF * i for i in range(5))
     C = [A + BUF * (5 + i) for i in range(3)]

@@ -491,6 +491,41 @@ def test_coalesced_reduce_scatter_accum_is_bit_exact(orc, gen, p, k, numels, ali
         assert acc.guards_intact()
 
 
+@pytest.mark.parametrize("name", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("p,k,numels,align,threshold", [
+    (16, 8, [512 * 16, 16 * 20000, 16 * 8], 8, 0), (8, 8, [1000, 77, 5000, 3], 1, 0),
+    (5, 5, [30001, 24, 7], 1, 1), (8, 8, [8 * 4096, 8 * 40], 8, 1), (6, 3, [64 * 6 + 1] * 60, 1, 0),
+])
+def test_typed_coalesced_reduce_scatter_accum_is_bit_exact(orc, gen, name, p, k, numels, align, threshold):
+    """The coalesced reduction for bf16, binary16 and binary32 gradient buffers; threshold 1
+    forces the streaming kernels."""
+    dtype = {"bf16": mics.MICS_DTYPE_BF16, "f16": mics.MICS_DTYPE_F16, "f32": mics.MICS_DTYPE_F32}[name]
+    code = {"bf16": orc.DTYPE_BF16, "f16": orc.DTYPE_F16, "f32": orc.DTYPE_F32}[name]
+    tab = (gen.normal_table(1e-3, "bf16") if name == "bf16" else
+           gen.normal_table(3e-5, "f32").astype(np.float16).view(np.uint16) if name == "f16" else
+           gen.normal_table(1e-3, "f32"))
+    np_dt = np.float32 if name == "f32" else np.uint16
+    lay = gen.coalesced_layout(numels, p, k, align=align)
+    total = lay.grad_off[-1]
+    try:
+        mics.mics_set_stream_threshold_bytes(threshold)
+        for rank in (0, p - 1):
+            segs = lay.reduce_segments(rank)
+            acc = Guarded(lay.shard_off[-1], np.float32)
+            ref = np.full(lay.shard_off[-1], np.nan, np.float32)
+            for t_step in range(2):
+                host = [gen.fill_host(gen.stream_key(810, gen.ROLE_GRAD, 0, t_step, q), 0, total, tab)
+                        for q in range(p)]
+                dev = [Guarded(total, np_dt, fill=h) for h in host]
+                mics.mics_reduce_scatter_accum_coalesced_typed(acc.t, [d.t for d in dev], segs, t_step > 0, dtype)
+                torch.cuda.synchronize()
+                orc.reduce_scatter_accum_coalesced_typed(ref, host, segs, t_step > 0, code)
+            assert np.array_equal(acc.numpy().view(np.uint32), ref.view(np.uint32))
+            assert acc.guards_intact()
+    finally:
+        mics.mics_set_stream_threshold_bytes(0)
+
+
 # ---- fused replica average + Adam -------------------------------------------------------------------
 
 @pytest.mark.parametrize("r,count,skew,want_bf16", [

@@ -53,3 +53,23 @@ def test_coalesced_reduce_equals_per_tensor_integer_sums(orc, gen):
                 lo = lay.grad_off[t] + g * lay.S[t]
                 want[lay.shard_off[t]:lay.shard_off[t] + lay.S[t]] += sum(w[lo:lo + lay.S[t]] for w in wide)
         assert np.array_equal(acc.astype(np.int64), want)
+
+
+def test_typed_coalesced_reduce_equals_per_tensor_integer_sums_in_every_format(orc, gen):
+    p, k = 4, 2
+    numels = [100, 8, 33, 64]
+    lay = gen.coalesced_layout(numels, p, k, align=1)
+    table = gen.small_int_table(-8, 8, "f32")
+    total = lay.grad_off[-1]
+    g = 2
+    f32 = [gen.fill_host(gen.stream_key(42, gen.ROLE_GRAD, 0, 0, q), 0, total, table) for q in range(p)]
+    want = np.zeros(lay.shard_off[-1], np.int64)
+    for t in range(len(numels)):
+        lo = lay.grad_off[t] + g * lay.S[t]
+        want[lay.shard_off[t]:lay.shard_off[t] + lay.S[t]] = 1 + sum(w[lo:lo + lay.S[t]].astype(np.int64) for w in f32)
+    variants = {orc.DTYPE_F32: f32, orc.DTYPE_F16: [x.astype(np.float16).view(np.uint16) for x in f32],
+                orc.DTYPE_BF16: [orc.bf16_narrow(x) for x in f32]}
+    for dtype, grads in variants.items():
+        acc = np.ones(lay.shard_off[-1], np.float32)
+        orc.reduce_scatter_accum_coalesced_typed(acc, grads, lay.reduce_segments(g), True, dtype)
+        assert np.array_equal(acc.astype(np.int64), want), dtype
