@@ -272,3 +272,62 @@ def test_coalesced_layer_full_size_h8192(orc, gen):
                 orc.reduce_scatter_accum(ref, host, 0, ts > 0)
             got = acc[lay.shard_off[t] + a:lay.shard_off[t] + b].cpu().numpy()
             assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), (t, a, b)
+
+
+def test_binary16_pipeline_full_size_h8192(orc, gen):
+    """Mixed precision without bf16 (the paper's V100 runs, Section 5) on the h = 8192 shard:
+    loss-scaled binary16 gradients through the typed reduction, the loss scale undone in the
+    averaging factor, and the fused average + Adam step writing binary16 parameters."""
+    cfg = gen.CONFIGS["h8192"]
+    p, r, s, count, rank = cfg.p, cfg.r, 3, cfg.S, 9
+    offset = rank * cfg.S
+    loss_scale = 1024.0
+    tb = Tables(gen, cfg)
+    tb.host["grad16"] = gen.normal_table(cfg.sigma_grad * loss_scale, "f32").astype(np.float16).view(np.uint16)
+    tb.dev["grad16"] = torch.from_numpy(tb.host["grad16"].view(np.int16)).to(DEV)
+    tb.host["acc16"] = gen.normal_table(cfg.sigma_grad * loss_scale * (p * s) ** 0.5, "f32")
+    tb.dev["acc16"] = torch.from_numpy(tb.host["acc16"]).to(DEV)
+    hp = dict(lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps, weight_decay=cfg.weight_decay)
+    scale = float(np.float32(1.0 / (r * p * s * loss_scale)))
+    grads = torch.empty((p, count), dtype=torch.int16, device=DEV)
+    acc = torch.full((count,), float("nan"), dtype=torch.float32, device=DEV)
+    for t in range(s):
+        for q in range(p):
+            tb.fill_dev(grads[q], grad_key(gen, cfg, 7, t, q), offset, "grad16")
+        mics.mics_reduce_scatter_accum_typed(acc, [grads[q] for q in range(p)], 0, count, t > 0, mics.MICS_DTYPE_F16)
+    others = [torch.empty(count, dtype=torch.float32, device=DEV) for _ in range(r - 1)]
+    for c in range(1, r):
+        tb.fill_dev(others[c - 1], gen.stream_key(cfg.seed, gen.ROLE_ACC, 7, c), offset, "acc16")
+    master = torch.empty(count, dtype=torch.float32, device=DEV)
+    tb.fill_dev(master, gen.stream_key(cfg.seed, gen.ROLE_MASTER), offset, "master")
+    m = torch.zeros(count, dtype=torch.float32, device=DEV)
+    v = torch.zeros(count, dtype=torch.float32, device=DEV)
+    ph = torch.empty(count, dtype=torch.int16, device=DEV)
+    mics.mics_replica_average_adam_shard_typed(master, m, v, ph, mics.MICS_DTYPE_F16, [acc] + others, count, scale,
+                                               step=1, **hp)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(acc).all())
+    checked = 0
+    for a, b in windows(count, extra_points=[count // 2], seed=77):
+        n = b - a
+        acc_ref = np.empty(n, np.float32)
+        for t in range(s):
+            host = [tb.fill_host(grad_key(gen, cfg, 7, t, q), offset + a, n, "grad16") for q in range(p)]
+            orc.reduce_scatter_accum_typed(acc_ref, host, 0, t > 0, orc.DTYPE_F16)
+        assert np.array_equal(acc[a:b].cpu().numpy().view(np.uint32), acc_ref.view(np.uint32)), a
+        copies = [acc_ref] + [tb.fill_host(gen.stream_key(cfg.seed, gen.ROLE_ACC, 7, c), offset + a, n, "acc16")
+                              for c in range(1, r)]
+        avg_ref = orc.replica_average(copies, scale)
+        w0 = tb.fill_host(gen.stream_key(cfg.seed, gen.ROLE_MASTER), offset + a, n, "master")
+        w32, m32, v32 = w0.copy(), np.zeros(n, np.float32), np.zeros(n, np.float32)
+        p32 = orc.adam_shard(w32, m32, v32, avg_ref, step=1, f32=True, param_dtype="f16", **hp)
+        w64, m64, v64 = w0.copy(), np.zeros(n, np.float32), np.zeros(n, np.float32)
+        orc.adam_shard(w64, m64, v64, avg_ref, step=1, want_bf16=False, **hp)
+        gw = master[a:b].cpu().numpy()
+        assert adam_rel_err(gw, w64, w0).max() <= 1e-6
+        assert np.array_equal(gw.view(np.uint32), w32.view(np.uint32))
+        assert np.array_equal(m[a:b].cpu().numpy().view(np.uint32), m32.view(np.uint32))
+        assert np.array_equal(v[a:b].cpu().numpy().view(np.uint32), v32.view(np.uint32))
+        assert np.array_equal(ph[a:b].cpu().numpy().view(np.uint16), p32)
+        checked += n
+    assert checked >= min(count // 100, 6 * WIN)
