@@ -32,9 +32,9 @@
  *     enqueues its kernel(s) on `stream` (a hipStream_t passed as void*;
  *     NULL = the default stream) and returns.  Work is ordered by that stream.
  *     No kernel uses scratch memory beyond the caller's buffers.
- *   - State between calls: the thread-local error text, and the two
- *     process-wide measurement knobs of mics_tuning.h (launch shape, cache-hint
- *     threshold), which never change a result.  Nothing else.
+ *   - State between calls: the thread-local error text, and the three
+ *     process-wide measurement knobs of mics_tuning.h (grid cap, launch shape,
+ *     cache-hint threshold), which never change a result.  Nothing else.
  *   - Arguments are validated before the first HIP call, so every argument
  *     error is reported without a GPU, and on an argument error nothing is
  *     enqueued.  MICS_ERR_HIP reports the status of the failed launch call

@@ -81,7 +81,7 @@ mics::AdamScalars adam_scalars(float lr, float beta1, float beta2, float eps, fl
 
 extern "C" {
 
-int mics_version(void) { return 210; }
+int mics_version(void) { return 300; }   // 0.3.0
 
 const char* mics_last_error(void) { return g_error; }
 
