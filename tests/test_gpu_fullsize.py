@@ -136,7 +136,7 @@ def test_reorder_full_size(orc, gen, name):
             assert int(src.to(torch.int64).sum()) == int(dst.to(torch.int64).sum())
 
 
-def run_rank_pipeline(orc, gen, cfg, rank, count, offset, boundaries=()):
+def run_rank_pipeline(orc, gen, cfg, rank, count, offset, boundaries=(), n_random=None):
     """s reduce-scatter-accumulates, the replica average and one Adam step on `count` elements
     starting at global element `offset`, checked on sampled windows."""
     p, r, s = cfg.p, cfg.r, cfg.s
@@ -167,7 +167,7 @@ def run_rank_pipeline(orc, gen, cfg, rank, count, offset, boundaries=()):
     # MICS_TEST_FULL=1 checks every element instead of sampled windows (minutes of oracle time)
     spans = ([(a, min(a + (1 << 22), count)) for a in range(0, count, 1 << 22)]
              if os.environ.get("MICS_TEST_FULL") == "1" else
-             windows(count, extra_points=[count // 2, *boundaries], seed=cfg.seed + rank))
+             windows(count, extra_points=[count // 2, *boundaries], seed=cfg.seed + rank, n_random=n_random))
     for a, b in spans:
         n = b - a
         acc_ref = np.empty(n, np.float32)
@@ -331,3 +331,40 @@ def test_binary16_pipeline_full_size_h8192(orc, gen):
         assert np.array_equal(ph[a:b].cpu().numpy().view(np.uint16), p32)
         checked += n
     assert checked >= min(count // 100, 6 * WIN)
+
+
+def test_element_indices_beyond_32_bits(orc, gen):
+    """The largest calls: more than 2^32 elements per buffer, so that element indices, byte offsets
+    and lane counts all leave 32 bits.  Windows at both ends, around 2^31 and 2^32 and at random."""
+    n = (1 << 32) + 4096 + 40
+    # reorder: 4 chunks of 2^30 + 1034 elements (byte offsets of the later chunks exceed 2^32)
+    p, k = 4, 2
+    S = n // p
+    assert S * p == n
+    cfg = gen.Config("beyond32", n - 5, p=p, k=k, r=2, s=2, sigma_grad=1e-3, seed=1099)
+    tb = Tables(gen, cfg)
+    nodes = p // k
+    W = torch.empty(n, dtype=torch.int16, device=DEV)
+    for g in range(p):
+        j, l = divmod(g, k)
+        slot = (l * nodes + j) * S
+        tb.fill_dev(W[slot:slot + S], gen.stream_key(cfg.seed, gen.ROLE_PARAM, 0, 0, g), 0, "param")
+    F = torch.full((n,), 0x5A5A, dtype=torch.int16, device=DEV)
+    mics.mics_hier_gather_reorder(F, [W[l * nodes * S:(l + 1) * nodes * S] for l in range(k)], cfg.N, S, p, k, 2)
+    torch.cuda.synchronize()
+    assert bool((F[cfg.N:] == 0x5A5A).all())
+    for a, b in windows(cfg.N, extra_points=[g * S for g in range(1, p)] + [1 << 31, 1 << 32], seed=5, n_random=6):
+        got = F[a:b].cpu().numpy().view(np.uint16)
+        parts, x = [], a
+        while x < b:
+            g, i = divmod(x, S)
+            m = min(b - x, S - i)
+            parts.append(tb.fill_host(gen.stream_key(cfg.seed, gen.ROLE_PARAM, 0, 0, g), i, m, "param"))
+            x += m
+        assert np.array_equal(got, np.concatenate(parts)), (a, b)
+    del W, F
+    torch.cuda.empty_cache()
+    # reduce (p = 2 buffers, 2 micro-steps), average over 2 copies, Adam: one call of n - 3 elements each
+    cfg2 = gen.Config("beyond32", n, p=2, k=2, r=2, s=2, sigma_grad=1e-3, seed=1098)
+    checked = run_rank_pipeline(orc, gen, cfg2, 0, n - 3, 16, boundaries=[1 << 31, 1 << 32], n_random=6)
+    assert checked >= 8 * WIN
