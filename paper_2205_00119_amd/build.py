@@ -33,6 +33,22 @@ def build(extra_flags=(), out: str = LIB, verbose: bool = False) -> str:
     return out
 
 
+EXAMPLE_SRC = os.path.join(HERE, "examples", "step_from_c.cpp")
+EXAMPLE_BIN = os.path.join(HERE, "examples", "step_from_c")
+
+
+def build_example(out: str = EXAMPLE_BIN) -> str:
+    """The plain host program that drives libmics.so through its C ABI (no Python, no PyTorch)."""
+    tmp = out + f".tmp{os.getpid()}"
+    cmd = [HIPCC, "--offload-arch=gfx950", "-O2", "-std=c++17", EXAMPLE_SRC,
+           "-I" + os.path.join(HERE, "..", "include"), "-L" + HERE, "-lmics", "-Wl,-rpath,$ORIGIN/..", "-o", tmp]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+    os.replace(tmp, out)
+    return out
+
+
 if __name__ == "__main__":
     import sys
     # usage: build.py [out.so] [-DNAME=VALUE ...]   (variants for measurements)
