@@ -301,15 +301,29 @@ constexpr int kSegLanes = MICS_SEG_BLOCK;
 #endif
 constexpr int kMaxSeg = kMaxSegPerLaunch;
 
-// Index of the segment whose tile range holds workgroup x: tile_begin is ascending, unused
-// entries hold 0xFFFFFFFF.  Counting instead of walking keeps the table reads independent of
-// one another (a few wide scalar loads), which matters for workgroups that move only 4 KiB.
-__device__ __forceinline__ int segment_of(const unsigned (&tile_begin)[kMaxSeg + 1], unsigned x)
+// Index of the segment whose tile range holds workgroup x (x < 2^31 - 1): tile_begin is
+// ascending, entries from n on hold kNoTile.  Counting instead of walking keeps the table reads
+// independent of one another (a few wide scalar loads), which matters for workgroups that move
+// only a few KiB; the count is written as integer arithmetic on the sign bit so that it stays
+// on the scalar unit (as a sum of comparisons it was compiled into some 300 vector
+// instructions per wavefront: -18 % on a layer of 16 unaligned tensors), and only the
+// sixteens of entries in use are counted.
+constexpr unsigned kNoTile = 0x7FFFFFFFu;
+__device__ __forceinline__ int segment_of(const unsigned (&tile_begin)[kMaxSeg + 1], int n, unsigned x)
 {
-    int t = 0;
+    static_assert(kMaxSeg == 48, "three sixteens");
+    unsigned t = 0;
     #pragma unroll
-    for (int i = 1; i < kMaxSeg; ++i) t += tile_begin[i] <= x ? 1 : 0;
-    return t;
+    for (int i = 1; i < 16; ++i) t += (tile_begin[i] - 1u - x) >> 31;      // 1 iff tile_begin[i] <= x
+    if (n > 16) {
+        #pragma unroll
+        for (int i = 16; i < 32; ++i) t += (tile_begin[i] - 1u - x) >> 31;
+    }
+    if (n > 32) {
+        #pragma unroll
+        for (int i = 32; i < 48; ++i) t += (tile_begin[i] - 1u - x) >> 31;
+    }
+    return (int)t;
 }
 struct ReorderSeg {
     unsigned long long shard_vecs, valid_bytes, src_vec, dst_vec;
@@ -324,7 +338,7 @@ __global__ __launch_bounds__(kMaxBlock) void reorder_seg_kernel(
     u32x4* __restrict__ dst, PtrTable src, ReorderSegTable tab, int k)
 {
     const unsigned x = blockIdx.x;
-    const int t = segment_of(tab.tile_begin, x);
+    const int t = segment_of(tab.tile_begin, tab.n, x);
     const size_t shard_vecs = tab.seg[t].shard_vecs, valid_bytes = tab.seg[t].valid_bytes;
     const size_t g = blockIdx.y;
     const size_t chunk_begin = g * shard_vecs * 16;
@@ -372,7 +386,7 @@ struct ByteSegTable {
     ByteSeg seg[kMaxSeg];
     __device__ __forceinline__ const ByteSeg& locate(unsigned x, size_t* tile) const
     {
-        const int t = segment_of(tile_begin, x);
+        const int t = segment_of(tile_begin, n, x);
         *tile = x - tile_begin[t];
         return seg[t];
     }
@@ -742,7 +756,7 @@ __global__ __launch_bounds__(kMaxBlock) void rsa_seg_kernel(
 {
     constexpr int EPL = 4 * GradFormat<KIND>::kPerDword;
     const unsigned x = blockIdx.x;
-    const int t = segment_of(tab.tile_begin, x);
+    const int t = segment_of(tab.tile_begin, tab.n, x);
     const size_t end = tab.seg[t].end, lead = tab.seg[t].lead;
     const size_t v0 = ((size_t)(x - tab.tile_begin[t]) * blockDim.x + threadIdx.x) * EPL;
     if (x == tab.tile_begin[t]) rsa_edges<KIND, EPL, ACCUM>(acc + tab.seg[t].dst, g, p, tab.seg[t].src0, lead, end);
@@ -1310,7 +1324,7 @@ int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs
                 tiles += (tab.seg[t].shard_vecs + tile_vecs - 1) / tile_vecs;
                 if (tiles > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
             }
-            for (int t = nt; t <= kMaxSeg; ++t) tab.tile_begin[t] = 0xFFFFFFFFu;
+            for (int t = nt; t <= kMaxSeg; ++t) tab.tile_begin[t] = kNoTile;
             if (tiles == 0) continue;
             if (int e = launch(reorder_seg_kernel, dim3((unsigned)tiles, (unsigned)p), dim3(sh.lanes), lds_for(sh), st,
                                (u32x4*)dst, src, tab, k))
@@ -1352,7 +1366,7 @@ int launch_reorder_coalesced(void* dst, const PtrTable& src, const Segment* segs
                 tiles += tiles_of(tab.seg[t]);
                 if (tiles > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
             }
-            for (int t = nt; t <= kMaxSeg; ++t) tab.tile_begin[t] = 0xFFFFFFFFu;
+            for (int t = nt; t <= kMaxSeg; ++t) tab.tile_begin[t] = kNoTile;
             if (tiles == 0) continue;
             if (int e = launch(reorder_shift_kernel<ByteSegTable>, dim3((unsigned)tiles, (unsigned)p), dim3(sh.lanes),
                                lds_for(sh), st, (unsigned char*)dst, src, tab, k))
@@ -1403,7 +1417,7 @@ int reduce_coalesced_kind(float* acc, PtrTable g, const Segment* segs, int n, in
             else tab.seg[t].end = 0;
             if (tiles > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
         }
-        for (int t = tab.n; t <= kMaxSeg; ++t) tab.tile_begin[t] = 0xFFFFFFFFu;
+        for (int t = tab.n; t <= kMaxSeg; ++t) tab.tile_begin[t] = kNoTile;
         if (tiles == 0) continue;
         const int err = dispatch2(accumulate, streamed, [&](auto A, auto SA) {
             // the streamed-accumulator kernels pass their results through 32 bytes of LDS per lane
