@@ -302,27 +302,19 @@ constexpr int kSegLanes = MICS_SEG_BLOCK;
 constexpr int kMaxSeg = kMaxSegPerLaunch;
 
 // Index of the segment whose tile range holds workgroup x (x < 2^31 - 1): tile_begin is
-// ascending, entries from n on hold kNoTile.  Counting instead of walking keeps the table reads
+// ascending, unused entries hold kNoTile.  Counting instead of walking keeps the table reads
 // independent of one another (a few wide scalar loads), which matters for workgroups that move
-// only a few KiB; the count is written as integer arithmetic on the sign bit so that it stays
-// on the scalar unit (as a sum of comparisons it was compiled into some 300 vector
-// instructions per wavefront: -18 % on a layer of 16 unaligned tensors), and only the
-// sixteens of entries in use are counted.
+// only a few KiB.  The count is written as integer arithmetic on the sign bit so that it stays
+// on the scalar unit: as a sum of comparisons it was compiled into some 300 vector
+// instructions per wavefront (-18 % on a layer of 16 unaligned tensors).  Counting only the
+// entries in use would need the entry count first, and that dependent load costs more than
+// the additions it saves (h = 8192 layer: 6.25 against 6.45 TB/s).
 constexpr unsigned kNoTile = 0x7FFFFFFFu;
-__device__ __forceinline__ int segment_of(const unsigned (&tile_begin)[kMaxSeg + 1], int n, unsigned x)
+__device__ __forceinline__ int segment_of(const unsigned (&tile_begin)[kMaxSeg + 1], unsigned x)
 {
-    static_assert(kMaxSeg == 48, "three sixteens");
     unsigned t = 0;
     #pragma unroll
-    for (int i = 1; i < 16; ++i) t += (tile_begin[i] - 1u - x) >> 31;      // 1 iff tile_begin[i] <= x
-    if (n > 16) {
-        #pragma unroll
-        for (int i = 16; i < 32; ++i) t += (tile_begin[i] - 1u - x) >> 31;
-    }
-    if (n > 32) {
-        #pragma unroll
-        for (int i = 32; i < 48; ++i) t += (tile_begin[i] - 1u - x) >> 31;
-    }
+    for (int i = 1; i < kMaxSeg; ++i) t += (tile_begin[i] - 1u - x) >> 31;      // 1 iff tile_begin[i] <= x
     return (int)t;
 }
 struct ReorderSeg {
@@ -338,7 +330,7 @@ __global__ __launch_bounds__(kMaxBlock) void reorder_seg_kernel(
     u32x4* __restrict__ dst, PtrTable src, ReorderSegTable tab, int k)
 {
     const unsigned x = blockIdx.x;
-    const int t = segment_of(tab.tile_begin, tab.n, x);
+    const int t = segment_of(tab.tile_begin, x);
     const size_t shard_vecs = tab.seg[t].shard_vecs, valid_bytes = tab.seg[t].valid_bytes;
     const size_t g = blockIdx.y;
     const size_t chunk_begin = g * shard_vecs * 16;
@@ -386,7 +378,7 @@ struct ByteSegTable {
     ByteSeg seg[kMaxSeg];
     __device__ __forceinline__ const ByteSeg& locate(unsigned x, size_t* tile) const
     {
-        const int t = segment_of(tile_begin, n, x);
+        const int t = segment_of(tile_begin, x);
         *tile = x - tile_begin[t];
         return seg[t];
     }
@@ -756,7 +748,7 @@ __global__ __launch_bounds__(kMaxBlock) void rsa_seg_kernel(
 {
     constexpr int EPL = 4 * GradFormat<KIND>::kPerDword;
     const unsigned x = blockIdx.x;
-    const int t = segment_of(tab.tile_begin, tab.n, x);
+    const int t = segment_of(tab.tile_begin, x);
     const size_t end = tab.seg[t].end, lead = tab.seg[t].lead;
     const size_t v0 = ((size_t)(x - tab.tile_begin[t]) * blockDim.x + threadIdx.x) * EPL;
     if (x == tab.tile_begin[t]) rsa_edges<KIND, EPL, ACCUM>(acc + tab.seg[t].dst, g, p, tab.seg[t].src0, lead, end);
