@@ -407,7 +407,9 @@ class Workload:
                 "value": round(b_step / (self.wall_unmarked / steps) / 1e9, 1),
                 "note": "the same number of steps after the timed region, no events between the kernels",
             },
+            # shard elements updated per second: over the whole step, and by the Adam kernel alone
             "elements_per_s": round(count / (ms_step * 1e-3), 1),
+            "elements_per_s_adam_kernel": round(count / (st["a4"]["mean"] * 1e-3), 1),
             "config": {
                 "workload": f"{cfg.name}: "
                             + (f"one transformer layer h={cfg.name[1:].split('_')[0]} " if cfg.name != "tiny"
@@ -491,7 +493,7 @@ def main():
     if args.view == "rank" and plain and not args.no_group_view and args.config != "tiny":
         gv = Workload(args, "group", mics, synth, torch, np).run(args.group_steps, 1)
         result["group_view"] = {key: gv[key] for key in ("value", "unit", "pct_of_peak_hbm", "steps", "warmup",
-                                                          "ms_per_step", "ms_per_step_events", "elements_per_s",
+                                                          "ms_per_step", "ms_per_step_events", "elements_per_s", "elements_per_s_adam_kernel",
                                                           "kernels", "roofline")}
         result["group_view"]["workload"] = gv["config"]["workload"]
         result["group_view"]["algorithmic_bytes_per_step"] = gv["config"]["algorithmic_bytes_per_step"]
