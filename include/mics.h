@@ -48,7 +48,7 @@
  *   - Pointers must be aligned to their element size; that is all the
  *     element-wise calls (reduce, average, Adam) need for full speed, except
  *     that bf16/fp16 gradient buffers of one call should all start at even or
- *     all at odd element addresses (otherwise about 20 % slower).  The reorder
+ *     all at odd element addresses (otherwise up to about 7 % slower).  The reorder
  *     runs at copy speed when every buffer and the shard size are multiples
  *     of 16 bytes and through a re-phasing kernel (about 8 % slower) otherwise.
  *   - Buffers of one call must not overlap unless stated.
