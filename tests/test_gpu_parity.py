@@ -670,6 +670,89 @@ def test_calls_are_stream_ordered_and_survive_hip_graph_capture(orc, gen):
             assert torch.equal(got, want), f"replay {replay} differs from the eager result"
 
 
+def test_every_kind_of_call_replays_from_a_hip_graph(orc, gen):
+    """The remaining entry points under capture: the unaligned and the coalesced gather, the
+    streaming and the coalesced typed reduction (pointer and segment tables are copied into the
+    launch at capture time: the host arrays are gone when the graph replays) and the fused typed
+    step.  Every replay must reproduce the oracle's results."""
+    p, k, S, r = 8, 4, 6001, 3                       # odd shard: the lane-shift gather
+    n = p * S - 3
+    nodes = p // k
+    shards = [tagged(gen, 980 + g, S, np.uint16) for g in range(p)]
+    T = [upload(orc.stage1_gather(shards, k, l)) for l in range(k)]
+    flat = torch.empty(p * S, dtype=torch.int16, device="cuda:0")
+    numels = [4096, 77, 10001, 64]
+    lay = gen.coalesced_layout(numels, p, k, align=1)
+    cshards = [[tagged(gen, 1980 + 50 * t + g, lay.S[t], np.uint16) for g in range(p)] for t in range(len(numels))]
+    CT_host = [np.concatenate([np.concatenate([cshards[t][j * k + l] for j in range(nodes)])
+                               for t in range(len(numels))]) for l in range(k)]
+    CT = [upload(t) for t in CT_host]
+    cflat = torch.empty(lay.flat_off[-1], dtype=torch.int16, device="cuda:0")
+    f16tab = gen.normal_table(3e-5, "f32").astype(np.float16).view(np.uint16)
+    g_host = [gen.fill_host(gen.stream_key(981, gen.ROLE_GRAD, 0, 0, q), 0, lay.grad_off[-1], f16tab) for q in range(p)]
+    g_dev = [upload(h) for h in g_host]
+    rank = 5
+    acc = torch.empty(lay.shard_off[-1], dtype=torch.float32, device="cuda:0")
+    acc2 = torch.empty(S, dtype=torch.float32, device="cuda:0")
+    copies_host = [gen.fill_host(gen.stream_key(982, gen.ROLE_ACC, c), 0, S, gen.normal_table(5e-3, "f32")) for c in range(r)]
+    copies = [upload(c) for c in copies_host]
+    w0_host = gen.fill_host(gen.stream_key(982, gen.ROLE_MASTER), 0, S, gen.normal_table(0.02, "f32"))
+    w0 = upload(w0_host)
+    w, m, v = torch.empty_like(w0), torch.empty_like(w0), torch.empty_like(w0)
+    ph = torch.empty(S, dtype=torch.int16, device="cuda:0")
+
+    def one_pass():
+        w.copy_(w0); m.fill_(0.0); v.fill_(0.0)
+        mics.mics_hier_gather_reorder(flat, list(T), n, S, p, k, 2)
+        mics.mics_hier_gather_reorder_coalesced(cflat, list(CT), list(lay.reorder_segments()), p, k, 2)
+        mics.mics_reduce_scatter_accum_coalesced_typed(acc, list(g_dev), list(lay.reduce_segments(rank)), False,
+                                                       mics.MICS_DTYPE_F16)
+        mics.mics_reduce_scatter_accum_typed(acc2, [g[:S] for g in g_dev], 0, S, False, mics.MICS_DTYPE_F16)
+        mics.mics_replica_average_adam_shard_typed(w, m, v, ph, mics.MICS_DTYPE_F16, list(copies), S, 0.25, step=2, **HP)
+
+    # the oracle's results
+    want_flat = orc.concat_shards(shards, n)
+    want_cflat = np.zeros(lay.flat_off[-1], np.uint16)
+    orc.hier_gather_reorder_coalesced(CT_host, lay.reorder_segments(), p, want_cflat)
+    want_acc = np.empty(lay.shard_off[-1], np.float32)
+    orc.reduce_scatter_accum_coalesced_typed(want_acc, g_host, lay.reduce_segments(rank), False, orc.DTYPE_F16)
+    want_acc2 = orc.reduce_scatter_accum_typed(np.empty(S, np.float32), [h[:S] for h in g_host], 0, False, orc.DTYPE_F16)
+    wr, mr, vr = w0_host.copy(), np.zeros(S, np.float32), np.zeros(S, np.float32)
+    want_ph = orc.adam_shard(wr, mr, vr, orc.replica_average(copies_host, 0.25), step=2, f32=True,
+                             param_dtype="f16", **HP)
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    try:
+        mics.mics_set_stream_threshold_bytes(1)          # the streaming kernels (LDS-staged stores)
+        with torch.cuda.stream(side):
+            one_pass()
+            with torch.cuda.graph(graph, stream=side):
+                one_pass()
+    finally:
+        mics.mics_set_stream_threshold_bytes(0)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for replay in range(3):
+        for x in (flat, cflat, ph):                      # eager work between the replays
+            x.fill_(replay + 1)
+        for x in (acc, acc2, w, m, v):
+            x.fill_(float(replay) - 3.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(flat.cpu().numpy().view(np.uint16)[:n], want_flat), replay
+        got_c = cflat.cpu().numpy().view(np.uint16)
+        for t in range(len(numels)):
+            a = lay.flat_off[t]
+            assert np.array_equal(got_c[a:a + numels[t]], want_cflat[a:a + numels[t]]), (replay, t)
+        assert np.array_equal(acc.cpu().numpy().view(np.uint32), want_acc.view(np.uint32)), replay
+        assert np.array_equal(acc2.cpu().numpy().view(np.uint32), want_acc2.view(np.uint32)), replay
+        assert np.array_equal(w.cpu().numpy().view(np.uint32), wr.view(np.uint32)), replay
+        assert np.array_equal(ph.cpu().numpy().view(np.uint16), want_ph), replay
+
+
 # ---- capped grids: every kernel's stride loop ---------------------------------------------------------
 
 def test_capped_grids_give_the_same_results(orc, gen):
