@@ -84,7 +84,7 @@ def parse_args():
                     help="before the steps, run one plain copy of known size (the reorder with "
                          "p = k = 1 over the whole layer: N bf16 read, N bf16 written) so that "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE can be scaled against it")
-    ap.add_argument("--cpu-sample", type=int, default=16 << 20,
+    ap.add_argument("--cpu-sample", type=int, default=32 << 20,
                     help="shard elements the CPU oracle is timed on")
     return ap.parse_args()
 
