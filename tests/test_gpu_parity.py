@@ -104,8 +104,13 @@ RSA_CASES = [
     (5, 30000, 16, 20001, 2, 0),
     (32, 20000, 160, 15000, 2, 0),            # cfg-4 group size
     (32, 150000, 160, 140003, 2, 0),          # ... beyond the small-message kernel: two batches of 16 loads
-    (128, 4096, 0, 4096, 1, 0),               # largest group (small message: one dword per lane)
+    (128, 4096, 0, 4096, 1, 0),               # largest group (small message: one dword per lane, two wavefronts)
     (128, 34000, 8, 33001, 1, 0),
+    (65, 9000, 3, 8190, 2, 1),                # smallest group of the two-wavefront form; odd offset, accumulator 4 bytes off
+    (100, 30000, 7, 29990, 2, 0),
+    (128, 2100, 1, 2000, 3, 3),
+    (96, 150000, 0, 150000, 2, 0),            # 14.4 M buffer elements: still the two-wavefront form
+    (96, 240000, 16, 230001, 2, 0),           # 22 M: the one-wavefront form, two rounds of loads
     (128, 280000, 8, 279001, 1, 0),           # largest group, 128-bit kernel: 8 batches of 16 loads
     (64, 40000, 64, 39000, 2, 0),             # 8 nodes of 8 (the paper's 50B-parameter group)
     (64, 9000, 3, 8190, 2, 1),                # small message, odd offset, accumulator off by 4 bytes
